@@ -1,0 +1,174 @@
+/*
+ * hero.h -- C ABI of the MI355X (gfx950) implementation of HERO's cached DiT
+ * denoising step (patch-wise refresh in shallow layers, linear extrapolation
+ * in deep layers; paper Sec. 3.3, 3.4, Alg. 1).
+ *
+ * Conventions (all entry points)
+ *   - Every function returns an int status (HERO_OK = 0 or a HERO_ERR_* code).
+ *     hero_last_error() returns a thread-local human-readable message for the
+ *     last non-zero status on the calling thread.  Nothing throws across the ABI.
+ *   - "dev" pointers are device (HBM) pointers of the current HIP device, "host"
+ *     pointers are ordinary host memory.  The library never allocates or frees
+ *     device memory: the caller passes a cache buffer and a workspace buffer,
+ *     sized by hero_cache_bytes(), and keeps them alive while the handle lives.
+ *   - All device work is enqueued on the caller's stream (a hipStream_t passed
+ *     as void*, NULL = the default stream) and is asynchronous; the library
+ *     never synchronises.  Calls on one handle must be issued in program order
+ *     on one stream (or on streams the caller orders).
+ *   - Token rows: the joint sequence has N = n_text + frames*height*width rows;
+ *     text rows come first, video token (t, y, x) sits at row
+ *     n_text + (t*height + y)*width + x.  Activations x are [N, hidden]
+ *     row-major, fp32 or bf16 according to resid_dtype, updated in place.
+ *   - Parameters (weights, biases, LayerNorm gain/bias) are bf16.  Linear
+ *     weights are [out_features, in_features] row-major.
+ *   - Caches are bf16.  Per layer the library keeps S = G_attn + G_ffn, the sum
+ *     of the two residual-branch features the paper caches (Eq. 2), for all N
+ *     rows; shallow layers (l < n_shallow) also keep K [N, hidden] and V
+ *     transposed [hidden, N_pad]; deep layers keep S of the previous full step
+ *     as well (the paper's Delta G = G_t - G_{t+M}, Sec. 3.4).
+ */
+#ifndef HERO_H_
+#define HERO_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  HERO_OK = 0,
+  HERO_ERR_INVALID_ARG = 1,      /* null pointer, out-of-range layer/step/k, bad enum      */
+  HERO_ERR_SHAPE = 2,            /* configuration the kernels do not support               */
+  HERO_ERR_STATE = 3,            /* e.g. refresh before the layer's cache was filled       */
+  HERO_ERR_BUFFER_TOO_SMALL = 4, /* caller's cache / workspace buffer is too small         */
+  HERO_ERR_HIP = 5               /* a HIP runtime call or kernel launch failed             */
+};
+
+enum { HERO_DTYPE_BF16 = 0, HERO_DTYPE_FP32 = 1 };
+
+/* Plain-data configuration, copied at hero_cache_create(). */
+typedef struct hero_config {
+  int32_t n_layers;    /* L                                                              */
+  int32_t n_shallow;   /* K: layers 0..K-1 refresh, K..L-1 extrapolate (Alg. 1)          */
+  int32_t interval;    /* M: a full step when step % M == 0                              */
+  int32_t hidden;      /* d, multiple of 64                                              */
+  int32_t n_heads;     /* hidden == n_heads * head_dim                                   */
+  int32_t head_dim;    /* 32 or 64                                                       */
+  int32_t ffn_dim;     /* multiple of 64                                                 */
+  int32_t frames, height, width;  /* video token grid f x h' x w'                         */
+  int32_t n_text;      /* text rows, placed first                                        */
+  int32_t patch_h, patch_w;       /* spatial patch of Eq. 4 (edge patches are clipped)    */
+  float   ratio;       /* R of Eq. 4; tokens per patch = clamp(floor(R*|P|+1/2),1,|P|)   */
+  int32_t resid_dtype; /* dtype of x: HERO_DTYPE_FP32 or HERO_DTYPE_BF16                 */
+  float   ln_eps;
+  uint64_t seed;       /* selection seed                                                 */
+} hero_config;
+
+/* Borrowed device pointers to one block's parameters (bf16). */
+typedef struct hero_layer_weights {
+  const void *ln1_g, *ln1_b;   /* [hidden]                */
+  const void *w_qkv, *b_qkv;   /* [3*hidden, hidden], [3*hidden]; rows: Q, then K, then V outputs */
+  const void *w_o, *b_o;       /* [hidden, hidden], [hidden]   */
+  const void *ln2_g, *ln2_b;   /* [hidden]                */
+  const void *w_ff1, *b_ff1;   /* [ffn_dim, hidden], [ffn_dim] */
+  const void *w_ff2, *b_ff2;   /* [hidden, ffn_dim], [hidden]  */
+} hero_layer_weights;
+
+typedef struct hero_cache* hero_cache_t;   /* opaque host-side handle owned by the library */
+
+const char* hero_last_error(void);
+
+/* Number of rows a cached step refreshes (|S(z)| of Eq. 4) for this configuration. */
+int hero_num_selected(const hero_config* cfg, int32_t* n_sel_host);
+
+/* Bytes of device memory the handle needs: cache (persistent features, K/V,
+ * token ages) and workspace (per-call temporaries). */
+int hero_cache_bytes(const hero_config* cfg, size_t* cache_bytes, size_t* workspace_bytes);
+
+/* Carves the caller's two device buffers (256-byte aligned) into slabs and
+ * enqueues their zero-fill on `stream`.  Ownership of the buffers stays with
+ * the caller.  Errors: INVALID_ARG, SHAPE, BUFFER_TOO_SMALL, HIP. */
+int hero_cache_create(const hero_config* cfg, void* dev_cache, size_t cache_bytes,
+                      void* dev_workspace, size_t workspace_bytes, void* stream,
+                      hero_cache_t* out);
+
+/* Frees the host-side handle only. */
+int hero_cache_destroy(hero_cache_t c);
+
+/* Start a new video: token ages = 0, no cached generations (Alg. 1 restarts). */
+int hero_cache_reset(hero_cache_t c, void* stream);
+
+/* Registers (borrows) the parameters of one layer. */
+int hero_set_layer_weights(hero_cache_t c, int32_t layer, const hero_layer_weights* w);
+
+/* Alg. 1 "Initial Caching" for one layer (Eq. 2 on all N rows): x <- block(x),
+ * cache S = G_attn + G_ffn for all rows, K/V for shallow layers; deep layers
+ * first move the current S to the previous generation. */
+int hero_full_layer(hero_cache_t c, int32_t layer, void* dev_x, void* stream);
+
+/* S(z) of Eq. 4 with frequency-aware tracking (Sec. 3.3): writes n_sel row
+ * indices (int32, joint-sequence rows, patch-major, decreasing priority inside
+ * a patch) to dev_idx and updates the token ages.  n_sel_host (optional)
+ * receives the count, which depends on the configuration only. */
+int hero_select(hero_cache_t c, int32_t step, int32_t* dev_idx, int32_t* n_sel_host, void* stream);
+
+/* Sets every token age to zero (done by hero_step after a full step). */
+int hero_reset_ages(hero_cache_t c, void* stream);
+
+/* Eq. 3 / Alg. 1 (l < K): recompute QKV, attention against the full cached K/V,
+ * and FFN for the n_sel rows in dev_idx (unique, in [0, N)), scatter the
+ * results into the caches, then x += S on all N rows.  n_sel = 0 is pure reuse.
+ * Errors: STATE if the layer has not been filled, INVALID_ARG if layer >= K. */
+int hero_refresh_layer(hero_cache_t c, int32_t layer, void* dev_x, const int32_t* dev_idx,
+                       int32_t n_sel, void* stream);
+
+/* Eq. 5 / Alg. 1 (l >= K): x += S_t + (S_t - S_{t+M}) * k / M on all rows; the
+ * difference is taken as zero while only one full-step generation exists.
+ * 0 <= k <= M.  Errors: STATE if not filled, INVALID_ARG if layer < K. */
+int hero_extrapolate_layer(hero_cache_t c, int32_t layer, void* dev_x, int32_t k, void* stream);
+
+/* Alg. 1 for one denoising step: full step if step % M == 0 (every layer via
+ * hero_full_layer, then ages = 0), otherwise select once and run
+ * refresh (l < K) / extrapolate (l >= K) with k = step - last full step. */
+int hero_step(hero_cache_t c, void* dev_x, int32_t step, void* stream);
+
+/* Read-only views into the handle, for tests and tools.  `what`:
+ *   0 S_cur [N,hidden]   1 S_prev [N,hidden] (deep)   2 K [N,hidden] (shallow)
+ *   3 V^T [hidden,N_pad] (shallow)   4 ages int32 [n_video]   5 last idx int32 [n_sel]
+ * Returns the device pointer and the leading dimension in elements. */
+int hero_cache_view(hero_cache_t c, int32_t layer, int32_t what, void** dev_ptr, int64_t* ld);
+
+/* Schedule state: number of full steps taken and the index of the last one (-1 if none). */
+int hero_cache_state(hero_cache_t c, int32_t* n_full, int32_t* last_full_step);
+
+/* ---- building blocks, exposed so each kernel can be checked on its own ------------- */
+
+/* out[i,:] = LayerNorm(x[rows[i],:] (+ add[rows[i],:])) * gain + bias, bf16 out [n_rows, hidden].
+ * rows == NULL means rows[i] = i.  add may be NULL.  (Eq. 2's LN on gathered rows.) */
+int hero_gather_ln(const void* dev_x, int32_t x_dtype, const void* dev_add_bf16, const int32_t* dev_rows,
+                   int32_t n_rows, int32_t hidden, const void* gain, const void* bias, float eps,
+                   void* dev_out_bf16, void* stream);
+
+/* C[M,N] = act(A[M,K] W[N,K]^T + bias[N]) in bf16 with fp32 accumulation.
+ * act: 0 none, 1 tanh-GELU.  K % 64 == 0, N % 64 == 0. */
+int hero_linear(const void* dev_a, const void* dev_w, const void* dev_bias, void* dev_c,
+                int32_t m, int32_t n, int32_t k, int32_t act, void* stream);
+
+/* O[r,hidden] = softmax(Q K^T / sqrt(head_dim)) V per head; Q [r,hidden], K [n_keys,hidden],
+ * V given transposed as vt [hidden, ld_vt] with ld_vt >= n_keys, ld_vt % 64 == 0 and
+ * columns n_keys..ld_vt-1 finite (zero).  (FullAttn of Eq. 2 for refreshed queries, Eq. 3.) */
+int hero_attention(const void* dev_q, const void* dev_k, const void* dev_vt, int64_t ld_vt,
+                   void* dev_o, int32_t r, int32_t n_keys, int32_t n_heads, int32_t head_dim,
+                   void* stream);
+
+/* x[N,hidden] += (1+alpha) * s_cur - alpha * s_prev (Eq. 5 followed by the residual add);
+ * s_prev may be NULL (alpha is then ignored: plain x += s_cur, Eq. 3's merge-and-add). */
+int hero_axpy_features(void* dev_x, int32_t x_dtype, const void* s_cur, const void* s_prev,
+                       float alpha, int64_t n_elems, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HERO_H_ */

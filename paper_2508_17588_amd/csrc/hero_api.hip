@@ -1,0 +1,506 @@
+// Host side of the HERO library: cache handle, layer operations (fixed sequences of
+// kernel launches on the caller's stream) and the step schedule of Alg. 1.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <utility>
+#include <vector>
+
+#include "../../include/hero.h"
+#include "hero_kernels.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                      \
+  do {                                                                                     \
+    hipError_t e_ = (expr);                                                                \
+    if (e_ != hipSuccess) return fail(HERO_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+uint32_t fmix32_host(uint32_t h) {
+  h ^= h >> 16; h *= 0x85EBCA6Bu;
+  h ^= h >> 13; h *= 0xC2B2AE35u;
+  h ^= h >> 16;
+  return h;
+}
+
+// tokens per patch: clamp(floor(R*|P| + 1/2), 1, |P|), 0 if R <= 0 (R at float precision; the
+// product and the sum are exact in double)
+int tokens_per_patch(float ratio, int size) {
+  if (!(ratio > 0.f)) return 0;
+  double v = std::floor((double)ratio * (double)size + 0.5);
+  if (v < 1.0) v = 1.0;
+  if (v > (double)size) v = (double)size;
+  return (int)v;
+}
+
+int check_config(const hero_config* c) {
+  if (!c) return fail(HERO_ERR_INVALID_ARG, "config is null");
+  if (c->n_layers < 1 || c->n_shallow < 0 || c->n_shallow > c->n_layers || c->interval < 1)
+    return fail(HERO_ERR_INVALID_ARG, "need n_layers >= 1, 0 <= n_shallow <= n_layers, interval >= 1");
+  if (c->frames < 1 || c->height < 1 || c->width < 1 || c->n_text < 0 || c->patch_h < 1 || c->patch_w < 1)
+    return fail(HERO_ERR_INVALID_ARG, "token grid / patch sizes must be positive");
+  if (c->resid_dtype != HERO_DTYPE_FP32 && c->resid_dtype != HERO_DTYPE_BF16)
+    return fail(HERO_ERR_INVALID_ARG, "resid_dtype must be HERO_DTYPE_FP32 or HERO_DTYPE_BF16");
+  if (!(c->ratio >= 0.f) || !(c->ln_eps >= 0.f)) return fail(HERO_ERR_INVALID_ARG, "ratio and ln_eps must be >= 0");
+  if (c->head_dim != 32 && c->head_dim != 64) return fail(HERO_ERR_SHAPE, "head_dim must be 32 or 64");
+  if (c->hidden != c->n_heads * c->head_dim || c->n_heads < 1)
+    return fail(HERO_ERR_SHAPE, "hidden must equal n_heads * head_dim");
+  if (c->hidden % 64 != 0 || c->ffn_dim % 64 != 0 || c->ffn_dim < 64)
+    return fail(HERO_ERR_SHAPE, "hidden and ffn_dim must be multiples of 64");
+  if (c->hidden > 8192) return fail(HERO_ERR_SHAPE, "hidden must be <= 8192");
+  int64_t n = (int64_t)c->n_text + (int64_t)c->frames * c->height * c->width;
+  if (n > (1 << 24)) return fail(HERO_ERR_SHAPE, "more than 2^24 tokens");
+  return HERO_OK;
+}
+
+SelectGeom make_geom(const hero_config& c) {
+  SelectGeom g;
+  g.frames = c.frames; g.height = c.height; g.width = c.width; g.n_text = c.n_text;
+  g.patch_h = c.patch_h; g.patch_w = c.patch_w;
+  g.grid_h = (c.height + c.patch_h - 1) / c.patch_h;
+  g.grid_w = (c.width + c.patch_w - 1) / c.patch_w;
+  g.n_patches = c.frames * g.grid_h * g.grid_w;
+  int hh_last = c.height - (g.grid_h - 1) * c.patch_h;
+  int ww_last = c.width - (g.grid_w - 1) * c.patch_w;
+  g.n_take[0] = tokens_per_patch(c.ratio, c.patch_h * c.patch_w);
+  g.n_take[1] = tokens_per_patch(c.ratio, c.patch_h * ww_last);
+  g.n_take[2] = tokens_per_patch(c.ratio, hh_last * c.patch_w);
+  g.n_take[3] = tokens_per_patch(c.ratio, hh_last * ww_last);
+  g.take_per_full_row = (g.grid_w - 1) * g.n_take[0] + g.n_take[1];
+  int last_row = (g.grid_w - 1) * g.n_take[2] + g.n_take[3];
+  g.take_per_frame = (g.grid_h - 1) * g.take_per_full_row + last_row;
+  g.n_sel = c.frames * g.take_per_frame;
+  return g;
+}
+
+struct Layout {
+  int64_t n_tokens, n_video, n_pad;
+  size_t ages_off;
+  size_t layer_stride_shallow, layer_stride_deep;
+  size_t s_bytes, k_bytes, vt_bytes;
+  size_t cache_bytes;
+  // workspace
+  size_t idx_off, a_off, q_off, o_off, f_off, ktmp_off, vtmp_off, ws_bytes;
+};
+
+Layout make_layout(const hero_config& c) {
+  Layout L;
+  L.n_video = (int64_t)c.frames * c.height * c.width;
+  L.n_tokens = L.n_video + c.n_text;
+  L.n_pad = (int64_t)align_up((size_t)L.n_tokens, 64);
+  L.s_bytes = align_up((size_t)L.n_tokens * c.hidden * 2, 256);
+  L.k_bytes = L.s_bytes;
+  L.vt_bytes = align_up((size_t)c.hidden * L.n_pad * 2, 256);
+  L.ages_off = 0;
+  size_t off = align_up((size_t)L.n_video * 4, 256);
+  L.layer_stride_shallow = L.s_bytes + L.k_bytes + L.vt_bytes;
+  L.layer_stride_deep = 2 * L.s_bytes;
+  off += (size_t)c.n_shallow * L.layer_stride_shallow + (size_t)(c.n_layers - c.n_shallow) * L.layer_stride_deep;
+  L.cache_bytes = off;
+  size_t w = 0;
+  L.idx_off = w; w += align_up((size_t)L.n_tokens * 4, 256);
+  L.a_off = w; w += L.s_bytes;
+  L.q_off = w; w += L.s_bytes;
+  L.o_off = w; w += L.s_bytes;
+  L.f_off = w; w += align_up((size_t)L.n_tokens * c.ffn_dim * 2, 256);
+  L.ktmp_off = w; L.vtmp_off = w;
+  if (c.n_shallow < c.n_layers) {
+    w += L.k_bytes;
+    L.vtmp_off = w;
+    w += L.vt_bytes;
+  }
+  L.ws_bytes = w;
+  return L;
+}
+
+struct LayerState {
+  bf16_t* s_cur = nullptr;
+  bf16_t* s_prev = nullptr;   // deep only
+  bf16_t* k = nullptr;        // shallow only
+  bf16_t* vt = nullptr;       // shallow only
+  int fills = 0;
+  bool has_weights = false;
+  hero_layer_weights w;
+};
+
+}  // namespace
+
+struct hero_cache {
+  hero_config cfg;
+  Layout lay;
+  SelectGeom geom;
+  char* cache = nullptr;
+  char* ws = nullptr;
+  int32_t* ages = nullptr;
+  int32_t* idx = nullptr;
+  bf16_t *a = nullptr, *q = nullptr, *o = nullptr, *f = nullptr, *ktmp = nullptr, *vtmp = nullptr;
+  std::vector<LayerState> layers;
+  int n_full = 0;
+  int last_full = -1;
+  int last_n_sel = 0;
+};
+
+namespace {
+
+int check_handle(hero_cache_t c) {
+  if (!c) return fail(HERO_ERR_INVALID_ARG, "cache handle is null");
+  return HERO_OK;
+}
+
+int check_layer(hero_cache_t c, int layer) {
+  if (layer < 0 || layer >= c->cfg.n_layers)
+    return fail(HERO_ERR_INVALID_ARG, "layer %d out of range [0, %d)", layer, c->cfg.n_layers);
+  return HERO_OK;
+}
+
+// The block of Eq. 2 on the rows listed in `rows` (nullptr = all N rows), writing K/V to
+// (k_dst, vt_dst) and the branch features to s_dst; ends before the residual add.
+int run_block_rows(hero_cache_t c, LayerState& ls, void* x, const int32_t* rows, int n_rows, bf16_t* k_dst,
+                   bf16_t* vt_dst, bf16_t* s_dst, hipStream_t st) {
+  const hero_config& cfg = c->cfg;
+  const bool x_fp32 = cfg.resid_dtype == HERO_DTYPE_FP32;
+  const int d = cfg.hidden;
+  const hero_layer_weights& w = ls.w;
+  HIP_TRY(launch_gather_ln(x, x_fp32, nullptr, rows, n_rows, d, (const bf16_t*)w.ln1_g, (const bf16_t*)w.ln1_b,
+                           cfg.ln_eps, c->a, st));
+  GemmArgs g;
+  memset(&g, 0, sizeof(g));
+  g.a = c->a; g.w = (const bf16_t*)w.w_qkv; g.bias = (const bf16_t*)w.b_qkv;
+  g.m = n_rows; g.n = 3 * d; g.k = d; g.epilogue = EPI_QKV; g.rows = rows;
+  g.c = c->q; g.k_out = k_dst; g.vt_out = vt_dst; g.ld_vt = c->lay.n_pad; g.d = d;
+  HIP_TRY(launch_gemm(g, st));
+
+  AttnArgs at;
+  at.q = c->q; at.k = k_dst; at.vt = vt_dst; at.ld_vt = c->lay.n_pad; at.o = c->o;
+  at.r = n_rows; at.n_keys = (int)c->lay.n_tokens; at.n_heads = cfg.n_heads; at.head_dim = cfg.head_dim;
+  HIP_TRY(launch_attention(at, st));
+
+  memset(&g, 0, sizeof(g));
+  g.a = c->o; g.w = (const bf16_t*)w.w_o; g.bias = (const bf16_t*)w.b_o;
+  g.m = n_rows; g.n = d; g.k = d; g.epilogue = EPI_SCATTER; g.rows = rows; g.c = s_dst;
+  HIP_TRY(launch_gemm(g, st));
+
+  HIP_TRY(launch_gather_ln(x, x_fp32, s_dst, rows, n_rows, d, (const bf16_t*)w.ln2_g, (const bf16_t*)w.ln2_b,
+                           cfg.ln_eps, c->a, st));
+  memset(&g, 0, sizeof(g));
+  g.a = c->a; g.w = (const bf16_t*)w.w_ff1; g.bias = (const bf16_t*)w.b_ff1;
+  g.m = n_rows; g.n = cfg.ffn_dim; g.k = d; g.epilogue = EPI_GELU; g.c = c->f;
+  HIP_TRY(launch_gemm(g, st));
+
+  memset(&g, 0, sizeof(g));
+  g.a = c->f; g.w = (const bf16_t*)w.w_ff2; g.bias = (const bf16_t*)w.b_ff2;
+  g.m = n_rows; g.n = d; g.k = cfg.ffn_dim; g.epilogue = EPI_SCATTER_ADD; g.rows = rows; g.c = s_dst;
+  HIP_TRY(launch_gemm(g, st));
+  return HERO_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* hero_last_error(void) { return g_err; }
+
+int hero_num_selected(const hero_config* cfg, int32_t* n_sel_host) {
+  int rc = check_config(cfg);
+  if (rc) return rc;
+  if (!n_sel_host) return fail(HERO_ERR_INVALID_ARG, "n_sel_host is null");
+  *n_sel_host = make_geom(*cfg).n_sel;
+  return HERO_OK;
+}
+
+int hero_cache_bytes(const hero_config* cfg, size_t* cache_bytes, size_t* workspace_bytes) {
+  int rc = check_config(cfg);
+  if (rc) return rc;
+  if (!cache_bytes || !workspace_bytes) return fail(HERO_ERR_INVALID_ARG, "output pointer is null");
+  Layout L = make_layout(*cfg);
+  *cache_bytes = L.cache_bytes;
+  *workspace_bytes = L.ws_bytes;
+  return HERO_OK;
+}
+
+int hero_cache_create(const hero_config* cfg, void* dev_cache, size_t cache_bytes, void* dev_workspace,
+                      size_t workspace_bytes, void* stream, hero_cache_t* out) {
+  int rc = check_config(cfg);
+  if (rc) return rc;
+  if (!dev_cache || !dev_workspace || !out) return fail(HERO_ERR_INVALID_ARG, "null buffer or output pointer");
+  if (((uintptr_t)dev_cache | (uintptr_t)dev_workspace) & 255)
+    return fail(HERO_ERR_INVALID_ARG, "cache and workspace buffers must be 256-byte aligned");
+  Layout L = make_layout(*cfg);
+  if (cache_bytes < L.cache_bytes)
+    return fail(HERO_ERR_BUFFER_TOO_SMALL, "cache buffer has %zu bytes, %zu needed", cache_bytes, L.cache_bytes);
+  if (workspace_bytes < L.ws_bytes)
+    return fail(HERO_ERR_BUFFER_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes, L.ws_bytes);
+  hero_cache* c = new (std::nothrow) hero_cache();
+  if (!c) return fail(HERO_ERR_INVALID_ARG, "out of host memory");
+  c->cfg = *cfg;
+  c->lay = L;
+  c->geom = make_geom(*cfg);
+  c->cache = (char*)dev_cache;
+  c->ws = (char*)dev_workspace;
+  c->ages = (int32_t*)(c->cache + L.ages_off);
+  c->idx = (int32_t*)(c->ws + L.idx_off);
+  c->a = (bf16_t*)(c->ws + L.a_off);
+  c->q = (bf16_t*)(c->ws + L.q_off);
+  c->o = (bf16_t*)(c->ws + L.o_off);
+  c->f = (bf16_t*)(c->ws + L.f_off);
+  c->ktmp = (bf16_t*)(c->ws + L.ktmp_off);
+  c->vtmp = (bf16_t*)(c->ws + L.vtmp_off);
+  c->layers.resize(cfg->n_layers);
+  size_t off = align_up((size_t)L.n_video * 4, 256);
+  for (int l = 0; l < cfg->n_layers; ++l) {
+    LayerState& ls = c->layers[l];
+    ls.s_cur = (bf16_t*)(c->cache + off);
+    if (l < cfg->n_shallow) {
+      ls.k = (bf16_t*)(c->cache + off + L.s_bytes);
+      ls.vt = (bf16_t*)(c->cache + off + L.s_bytes + L.k_bytes);
+      off += L.layer_stride_shallow;
+    } else {
+      ls.s_prev = (bf16_t*)(c->cache + off + L.s_bytes);
+      off += L.layer_stride_deep;
+    }
+  }
+  hipStream_t st = (hipStream_t)stream;
+  hipError_t e = hipMemsetAsync(dev_cache, 0, L.cache_bytes, st);
+  if (e == hipSuccess) e = hipMemsetAsync(dev_workspace, 0, L.ws_bytes, st);
+  if (e != hipSuccess) {
+    delete c;
+    return fail(HERO_ERR_HIP, "hipMemsetAsync: %s", hipGetErrorString(e));
+  }
+  *out = c;
+  return HERO_OK;
+}
+
+int hero_cache_destroy(hero_cache_t c) {
+  if (check_handle(c)) return HERO_ERR_INVALID_ARG;
+  delete c;
+  return HERO_OK;
+}
+
+int hero_reset_ages(hero_cache_t c, void* stream) {
+  if (check_handle(c)) return HERO_ERR_INVALID_ARG;
+  HIP_TRY(launch_fill_i32(c->ages, 0, c->lay.n_video, (hipStream_t)stream));
+  return HERO_OK;
+}
+
+int hero_cache_reset(hero_cache_t c, void* stream) {
+  if (check_handle(c)) return HERO_ERR_INVALID_ARG;
+  for (auto& ls : c->layers) ls.fills = 0;
+  c->n_full = 0;
+  c->last_full = -1;
+  c->last_n_sel = 0;
+  return hero_reset_ages(c, stream);
+}
+
+int hero_set_layer_weights(hero_cache_t c, int32_t layer, const hero_layer_weights* w) {
+  if (check_handle(c)) return HERO_ERR_INVALID_ARG;
+  int rc = check_layer(c, layer);
+  if (rc) return rc;
+  if (!w) return fail(HERO_ERR_INVALID_ARG, "weights pointer is null");
+  const void* const* p = reinterpret_cast<const void* const*>(w);
+  for (size_t i = 0; i < sizeof(*w) / sizeof(void*); ++i) {
+    if (!p[i]) return fail(HERO_ERR_INVALID_ARG, "weight pointer %zu of layer %d is null", i, layer);
+    if ((uintptr_t)p[i] & 15) return fail(HERO_ERR_INVALID_ARG, "weight pointer %zu of layer %d is not 16-byte aligned", i, layer);
+  }
+  c->layers[layer].w = *w;
+  c->layers[layer].has_weights = true;
+  return HERO_OK;
+}
+
+int hero_full_layer(hero_cache_t c, int32_t layer, void* dev_x, void* stream) {
+  if (check_handle(c)) return HERO_ERR_INVALID_ARG;
+  int rc = check_layer(c, layer);
+  if (rc) return rc;
+  if (!dev_x) return fail(HERO_ERR_INVALID_ARG, "x is null");
+  LayerState& ls = c->layers[layer];
+  if (!ls.has_weights) return fail(HERO_ERR_STATE, "layer %d has no weights", layer);
+  hipStream_t st = (hipStream_t)stream;
+  const bool shallow = layer < c->cfg.n_shallow;
+  if (!shallow && ls.fills > 0) std::swap(ls.s_cur, ls.s_prev);   // G_{t+M} <- G_t (Sec. 3.4)
+  bf16_t* k_dst = shallow ? ls.k : c->ktmp;
+  bf16_t* vt_dst = shallow ? ls.vt : c->vtmp;
+  rc = run_block_rows(c, ls, dev_x, nullptr, (int)c->lay.n_tokens, k_dst, vt_dst, ls.s_cur, st);
+  if (rc) return rc;
+  HIP_TRY(launch_axpy_features(dev_x, c->cfg.resid_dtype == HERO_DTYPE_FP32, ls.s_cur, nullptr, 0.f,
+                               c->lay.n_tokens * c->cfg.hidden, st));
+  ls.fills += 1;
+  return HERO_OK;
+}
+
+int hero_select(hero_cache_t c, int32_t step, int32_t* dev_idx, int32_t* n_sel_host, void* stream) {
+  if (check_handle(c)) return HERO_ERR_INVALID_ARG;
+  if (step < 0) return fail(HERO_ERR_INVALID_ARG, "step must be >= 0");
+  if (!dev_idx && c->geom.n_sel > 0) return fail(HERO_ERR_INVALID_ARG, "dev_idx is null");
+  uint64_t seed = c->cfg.seed;
+  uint32_t s0 = (uint32_t)seed ^ (uint32_t)(seed >> 32);
+  uint32_t salt = fmix32_host(s0 + 0x9E3779B9u * ((uint32_t)step + 1u));
+  HIP_TRY(launch_select(c->geom, salt, c->ages, dev_idx, (hipStream_t)stream));
+  if (n_sel_host) *n_sel_host = c->geom.n_sel;
+  return HERO_OK;
+}
+
+int hero_refresh_layer(hero_cache_t c, int32_t layer, void* dev_x, const int32_t* dev_idx, int32_t n_sel,
+                       void* stream) {
+  if (check_handle(c)) return HERO_ERR_INVALID_ARG;
+  int rc = check_layer(c, layer);
+  if (rc) return rc;
+  if (!dev_x) return fail(HERO_ERR_INVALID_ARG, "x is null");
+  if (layer >= c->cfg.n_shallow)
+    return fail(HERO_ERR_INVALID_ARG, "layer %d is a deep layer (n_shallow = %d): it keeps no K/V cache", layer,
+                c->cfg.n_shallow);
+  if (n_sel < 0 || n_sel > c->lay.n_tokens) return fail(HERO_ERR_INVALID_ARG, "n_sel %d out of range", n_sel);
+  if (n_sel > 0 && !dev_idx) return fail(HERO_ERR_INVALID_ARG, "dev_idx is null");
+  LayerState& ls = c->layers[layer];
+  if (!ls.has_weights) return fail(HERO_ERR_STATE, "layer %d has no weights", layer);
+  if (ls.fills == 0) return fail(HERO_ERR_STATE, "layer %d refreshed before a full step filled its cache", layer);
+  hipStream_t st = (hipStream_t)stream;
+  if (n_sel > 0) {
+    rc = run_block_rows(c, ls, dev_x, dev_idx, n_sel, ls.k, ls.vt, ls.s_cur, st);
+    if (rc) return rc;
+  }
+  HIP_TRY(launch_axpy_features(dev_x, c->cfg.resid_dtype == HERO_DTYPE_FP32, ls.s_cur, nullptr, 0.f,
+                               c->lay.n_tokens * c->cfg.hidden, st));
+  return HERO_OK;
+}
+
+int hero_extrapolate_layer(hero_cache_t c, int32_t layer, void* dev_x, int32_t k, void* stream) {
+  if (check_handle(c)) return HERO_ERR_INVALID_ARG;
+  int rc = check_layer(c, layer);
+  if (rc) return rc;
+  if (!dev_x) return fail(HERO_ERR_INVALID_ARG, "x is null");
+  if (layer < c->cfg.n_shallow)
+    return fail(HERO_ERR_INVALID_ARG, "layer %d is a shallow layer (n_shallow = %d): it keeps one generation", layer,
+                c->cfg.n_shallow);
+  if (k < 0 || k > c->cfg.interval) return fail(HERO_ERR_INVALID_ARG, "k = %d outside [0, %d]", k, c->cfg.interval);
+  LayerState& ls = c->layers[layer];
+  if (ls.fills == 0) return fail(HERO_ERR_STATE, "layer %d extrapolated before a full step filled its cache", layer);
+  const bf16_t* prev = ls.fills >= 2 ? ls.s_prev : nullptr;
+  float alpha = (float)k / (float)c->cfg.interval;
+  HIP_TRY(launch_axpy_features(dev_x, c->cfg.resid_dtype == HERO_DTYPE_FP32, ls.s_cur, prev, alpha,
+                               c->lay.n_tokens * c->cfg.hidden, (hipStream_t)stream));
+  return HERO_OK;
+}
+
+int hero_step(hero_cache_t c, void* dev_x, int32_t step, void* stream) {
+  if (check_handle(c)) return HERO_ERR_INVALID_ARG;
+  if (!dev_x) return fail(HERO_ERR_INVALID_ARG, "x is null");
+  if (step < 0) return fail(HERO_ERR_INVALID_ARG, "step must be >= 0");
+  const hero_config& cfg = c->cfg;
+  int rc;
+  if (step % cfg.interval == 0) {
+    for (int l = 0; l < cfg.n_layers; ++l)
+      if ((rc = hero_full_layer(c, l, dev_x, stream)) != HERO_OK) return rc;
+    if ((rc = hero_reset_ages(c, stream)) != HERO_OK) return rc;
+    c->n_full += 1;
+    c->last_full = step;
+    c->last_n_sel = 0;
+    return HERO_OK;
+  }
+  if (c->n_full == 0) return fail(HERO_ERR_STATE, "cached step %d before any full step", step);
+  int k = step - c->last_full;
+  if (k < 1 || k > cfg.interval) return fail(HERO_ERR_STATE, "step %d is %d steps after the last full step %d", step, k, c->last_full);
+  int32_t n_sel = 0;
+  if ((rc = hero_select(c, step, c->idx, &n_sel, stream)) != HERO_OK) return rc;
+  c->last_n_sel = n_sel;
+  for (int l = 0; l < cfg.n_layers; ++l) {
+    rc = l < cfg.n_shallow ? hero_refresh_layer(c, l, dev_x, c->idx, n_sel, stream)
+                           : hero_extrapolate_layer(c, l, dev_x, k, stream);
+    if (rc) return rc;
+  }
+  return HERO_OK;
+}
+
+int hero_cache_view(hero_cache_t c, int32_t layer, int32_t what, void** dev_ptr, int64_t* ld) {
+  if (check_handle(c)) return HERO_ERR_INVALID_ARG;
+  if (!dev_ptr || !ld) return fail(HERO_ERR_INVALID_ARG, "output pointer is null");
+  if (what == 4) { *dev_ptr = c->ages; *ld = c->lay.n_video; return HERO_OK; }
+  if (what == 5) { *dev_ptr = c->idx; *ld = c->last_n_sel; return HERO_OK; }
+  int rc = check_layer(c, layer);
+  if (rc) return rc;
+  LayerState& ls = c->layers[layer];
+  switch (what) {
+    case 0: *dev_ptr = ls.s_cur; *ld = c->cfg.hidden; break;
+    case 1: *dev_ptr = ls.s_prev; *ld = c->cfg.hidden; break;
+    case 2: *dev_ptr = ls.k; *ld = c->cfg.hidden; break;
+    case 3: *dev_ptr = ls.vt; *ld = c->lay.n_pad; break;
+    default: return fail(HERO_ERR_INVALID_ARG, "unknown view %d", what);
+  }
+  if (!*dev_ptr) return fail(HERO_ERR_STATE, "layer %d keeps no such cache (view %d)", layer, what);
+  return HERO_OK;
+}
+
+int hero_cache_state(hero_cache_t c, int32_t* n_full, int32_t* last_full_step) {
+  if (check_handle(c)) return HERO_ERR_INVALID_ARG;
+  if (n_full) *n_full = c->n_full;
+  if (last_full_step) *last_full_step = c->last_full;
+  return HERO_OK;
+}
+
+// ---- building blocks ---------------------------------------------------------------
+
+int hero_gather_ln(const void* dev_x, int32_t x_dtype, const void* dev_add_bf16, const int32_t* dev_rows,
+                   int32_t n_rows, int32_t hidden, const void* gain, const void* bias, float eps,
+                   void* dev_out_bf16, void* stream) {
+  if (!dev_x || !gain || !bias || !dev_out_bf16) return fail(HERO_ERR_INVALID_ARG, "null pointer");
+  if (x_dtype != HERO_DTYPE_FP32 && x_dtype != HERO_DTYPE_BF16) return fail(HERO_ERR_INVALID_ARG, "bad x_dtype");
+  if (n_rows < 0) return fail(HERO_ERR_INVALID_ARG, "n_rows < 0");
+  if (hidden < 8 || hidden % 8 != 0 || hidden > 8192) return fail(HERO_ERR_SHAPE, "hidden must be a multiple of 8, <= 8192");
+  HIP_TRY(launch_gather_ln(dev_x, x_dtype == HERO_DTYPE_FP32, (const bf16_t*)dev_add_bf16, dev_rows, n_rows, hidden,
+                           (const bf16_t*)gain, (const bf16_t*)bias, eps, (bf16_t*)dev_out_bf16, (hipStream_t)stream));
+  return HERO_OK;
+}
+
+int hero_linear(const void* dev_a, const void* dev_w, const void* dev_bias, void* dev_c, int32_t m, int32_t n,
+                int32_t k, int32_t act, void* stream) {
+  if (!dev_a || !dev_w || !dev_bias || !dev_c) return fail(HERO_ERR_INVALID_ARG, "null pointer");
+  if (m < 0 || n <= 0 || k <= 0) return fail(HERO_ERR_INVALID_ARG, "bad sizes");
+  if (k % 64 != 0 || n % 64 != 0) return fail(HERO_ERR_SHAPE, "k and n must be multiples of 64");
+  if (act != 0 && act != 1) return fail(HERO_ERR_INVALID_ARG, "act must be 0 or 1");
+  GemmArgs g;
+  memset(&g, 0, sizeof(g));
+  g.a = (const bf16_t*)dev_a; g.w = (const bf16_t*)dev_w; g.bias = (const bf16_t*)dev_bias;
+  g.m = m; g.n = n; g.k = k; g.epilogue = act ? EPI_GELU : EPI_PLAIN; g.c = (bf16_t*)dev_c;
+  HIP_TRY(launch_gemm(g, (hipStream_t)stream));
+  return HERO_OK;
+}
+
+int hero_attention(const void* dev_q, const void* dev_k, const void* dev_vt, int64_t ld_vt, void* dev_o,
+                   int32_t r, int32_t n_keys, int32_t n_heads, int32_t head_dim, void* stream) {
+  if (!dev_q || !dev_k || !dev_vt || !dev_o) return fail(HERO_ERR_INVALID_ARG, "null pointer");
+  if (r < 0 || n_keys < 1 || n_heads < 1) return fail(HERO_ERR_INVALID_ARG, "bad sizes");
+  if (head_dim != 32 && head_dim != 64) return fail(HERO_ERR_SHAPE, "head_dim must be 32 or 64");
+  if (ld_vt % 64 != 0 || ld_vt < n_keys) return fail(HERO_ERR_SHAPE, "ld_vt must be a multiple of 64 and >= n_keys");
+  AttnArgs a;
+  a.q = (const bf16_t*)dev_q; a.k = (const bf16_t*)dev_k; a.vt = (const bf16_t*)dev_vt; a.ld_vt = ld_vt;
+  a.o = (bf16_t*)dev_o; a.r = r; a.n_keys = n_keys; a.n_heads = n_heads; a.head_dim = head_dim;
+  HIP_TRY(launch_attention(a, (hipStream_t)stream));
+  return HERO_OK;
+}
+
+int hero_axpy_features(void* dev_x, int32_t x_dtype, const void* s_cur, const void* s_prev, float alpha,
+                       int64_t n_elems, void* stream) {
+  if (!dev_x || !s_cur) return fail(HERO_ERR_INVALID_ARG, "null pointer");
+  if (x_dtype != HERO_DTYPE_FP32 && x_dtype != HERO_DTYPE_BF16) return fail(HERO_ERR_INVALID_ARG, "bad x_dtype");
+  if (n_elems < 0 || n_elems % 8 != 0) return fail(HERO_ERR_SHAPE, "n_elems must be a non-negative multiple of 8");
+  HIP_TRY(launch_axpy_features(dev_x, x_dtype == HERO_DTYPE_FP32, (const bf16_t*)s_cur, (const bf16_t*)s_prev, alpha,
+                               n_elems, (hipStream_t)stream));
+  return HERO_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,63 @@
+// Host-callable launchers of the HERO kernels (internal to the library).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef uint16_t bf16_t;
+
+// Patch grid of Eq. 4 and the closed-form output offsets of the selection list.
+// n_take[class]: tokens taken per patch; class = 2*(clipped bottom row) + (clipped right column).
+struct SelectGeom {
+  int32_t frames, height, width, n_text;
+  int32_t patch_h, patch_w;
+  int32_t grid_h, grid_w;        // patches per frame along y / x (ceil)
+  int32_t n_patches;             // frames * grid_h * grid_w
+  int32_t n_take[4];
+  int32_t take_per_full_row;     // picks of one patch-row that is not the last one
+  int32_t take_per_frame;
+  int32_t n_sel;                 // total picks
+};
+
+hipError_t launch_fill_i32(int32_t* p, int32_t v, int64_t n, hipStream_t st);
+hipError_t launch_select(const SelectGeom& g, uint32_t step_salt, int32_t* ages, int32_t* idx, hipStream_t st);
+hipError_t launch_gather_ln(const void* x, bool x_fp32, const bf16_t* add, const int32_t* rows, int n_rows,
+                            int hidden, const bf16_t* gain, const bf16_t* bias, float eps, bf16_t* out,
+                            hipStream_t st);
+hipError_t launch_axpy_features(void* x, bool x_fp32, const bf16_t* s_cur, const bf16_t* s_prev, float alpha,
+                                int64_t n_elems, hipStream_t st);
+
+// GEMM epilogues: what happens to act(A W^T + bias)
+enum GemmEpilogue {
+  EPI_PLAIN = 0,        // C[m, n]                       (ldc = n)
+  EPI_GELU = 1,         // C[m, n] = gelu_tanh(.)
+  EPI_QKV = 2,          // n < d: Q[m, n];  d <= n < 2d: K[row(m), n-d];  else V^T[n-2d, row(m)]
+  EPI_SCATTER = 3,      // S[row(m), n] = .
+  EPI_SCATTER_ADD = 4   // S[row(m), n] += .
+};
+
+struct GemmArgs {
+  const bf16_t* a;      // [M, K] row-major
+  const bf16_t* w;      // [N, K] row-major
+  const bf16_t* bias;   // [N]
+  int32_t m, n, k;
+  int32_t epilogue;
+  const int32_t* rows;  // row(m) = rows ? rows[m] : m   (scatter epilogues)
+  bf16_t* c;            // PLAIN/GELU: C; QKV: Q [M, d]; SCATTER*: S [*, n]
+  bf16_t* k_out;        // QKV: K cache [*, d]
+  bf16_t* vt_out;       // QKV: V^T cache [d, ld_vt]
+  int64_t ld_vt;
+  int32_t d;            // QKV: hidden
+};
+
+hipError_t launch_gemm(const GemmArgs& g, hipStream_t st);
+
+struct AttnArgs {
+  const bf16_t* q;      // [r, n_heads*head_dim]
+  const bf16_t* k;      // [n_keys, n_heads*head_dim]
+  const bf16_t* vt;     // [n_heads*head_dim, ld_vt]
+  int64_t ld_vt;
+  bf16_t* o;            // [r, n_heads*head_dim]
+  int32_t r, n_keys, n_heads, head_dim;
+};
+
+hipError_t launch_attention(const AttnArgs& a, hipStream_t st);

@@ -1,0 +1,208 @@
+// Bandwidth-bound row kernels of the cached DiT step: token selection (Eq. 4 with
+// age tracking), row gather + LayerNorm (Eq. 2's LN on the refreshed rows), and the
+// fused residual / extrapolation update over all rows (Eq. 3 merge-and-add, Eq. 5).
+#include "hero_device.h"
+#include "hero_kernels.h"
+
+// ---------------------------------------------------------------------------------
+// fill
+// ---------------------------------------------------------------------------------
+__global__ void fill_i32_kernel(int32_t* p, int32_t v, int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+hipError_t launch_fill_i32(int32_t* p, int32_t v, int64_t n, hipStream_t st) {
+  if (n <= 0) return hipSuccess;
+  int blocks = (int)((n + 255) / 256);
+  hipLaunchKernelGGL(fill_i32_kernel, dim3(blocks), dim3(256), 0, st, p, v, n);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------
+// selection: one thread per spatial patch
+// ---------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t fmix32(uint32_t h) {
+  h ^= h >> 16; h *= 0x85EBCA6Bu;
+  h ^= h >> 13; h *= 0xC2B2AE35u;
+  h ^= h >> 16;
+  return h;
+}
+
+__global__ void select_kernel(SelectGeom g, uint32_t step_salt, int32_t* __restrict__ ages,
+                              int32_t* __restrict__ idx) {
+  int p = blockIdx.x * blockDim.x + threadIdx.x;
+  if (p >= g.n_patches) return;
+  int per_frame = g.grid_h * g.grid_w;
+  int t = p / per_frame;
+  int rem = p - t * per_frame;
+  int py = rem / g.grid_w;
+  int px = rem - py * g.grid_w;
+  int y0 = py * g.patch_h, x0 = px * g.patch_w;
+  int hh = min(g.patch_h, g.height - y0);
+  int ww = min(g.patch_w, g.width - x0);
+  bool last_row = (py == g.grid_h - 1), last_col = (px == g.grid_w - 1);
+  int cls_row = last_row ? 1 : 0;
+  // tokens taken from this patch and where its picks go in the output list
+  int n_p = g.n_take[cls_row * 2 + (last_col ? 1 : 0)];
+  int out = t * g.take_per_frame + py * g.take_per_full_row + px * g.n_take[cls_row * 2];
+
+  int size = hh * ww;
+  uint64_t prev = ~0ull;      // keys are < 2^63, so this is above every key
+  uint64_t kmin = ~0ull;
+  for (int rank = 0; rank < n_p; ++rank) {
+    uint64_t best = 0; int best_tok = -1;
+    for (int e = 0; e < size; ++e) {
+      int dy = e / ww, dx = e - dy * ww;
+      int tok = (t * g.height + y0 + dy) * g.width + x0 + dx;
+      uint64_t key = ((uint64_t)(uint32_t)ages[tok] << 32) | fmix32(step_salt ^ ((uint32_t)tok * 0x85EBCA6Bu));
+      if (key < prev && (best_tok < 0 || key > best)) { best = key; best_tok = tok; }
+    }
+    idx[out + rank] = g.n_text + best_tok;
+    prev = best;
+    kmin = best;
+  }
+  for (int e = 0; e < size; ++e) {
+    int dy = e / ww, dx = e - dy * ww;
+    int tok = (t * g.height + y0 + dy) * g.width + x0 + dx;
+    int32_t a = ages[tok];
+    uint64_t key = ((uint64_t)(uint32_t)a << 32) | fmix32(step_salt ^ ((uint32_t)tok * 0x85EBCA6Bu));
+    ages[tok] = (n_p > 0 && key >= kmin) ? 0 : a + 1;
+  }
+}
+
+hipError_t launch_select(const SelectGeom& g, uint32_t step_salt, int32_t* ages, int32_t* idx, hipStream_t st) {
+  if (g.n_patches <= 0) return hipSuccess;
+  int blocks = (g.n_patches + 127) / 128;
+  hipLaunchKernelGGL(select_kernel, dim3(blocks), dim3(128), 0, st, g, step_salt, ages, idx);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------
+// gather + (optional add) + LayerNorm -> bf16 rows.  One wave per row.
+// ---------------------------------------------------------------------------------
+template <typename XT, int ITERS>
+__global__ __launch_bounds__(256) void gather_ln_kernel(
+    const XT* __restrict__ x, const bf16_t* __restrict__ add, const int32_t* __restrict__ rows,
+    int n_rows, int hidden, const bf16_t* __restrict__ gain, const bf16_t* __restrict__ bias,
+    float eps, bf16_t* __restrict__ out) {
+  int lane = threadIdx.x & 63;
+  int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= n_rows) return;
+  int64_t src = rows ? (int64_t)rows[r] : (int64_t)r;
+  const XT* xr = x + src * hidden;
+  const bf16_t* ar = add ? add + src * hidden : nullptr;
+  int n_chunks = hidden >> 3;
+  float v[ITERS][8];
+  float sum = 0.f;
+#pragma unroll
+  for (int it = 0; it < ITERS; ++it) {
+    int c = lane + it * 64;
+    if (c < n_chunks) {
+      ResidIO<XT>::load8(xr + c * 8, v[it]);
+      if (ar) {
+        float a8[8];
+        ResidIO<bf16_t>::load8(ar + c * 8, a8);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[it][j] += a8[j];
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) sum += v[it][j];
+    } else {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[it][j] = 0.f;
+    }
+  }
+  float mean = wave_sum(sum) / (float)hidden;
+  float sq = 0.f;
+#pragma unroll
+  for (int it = 0; it < ITERS; ++it) {
+    int c = lane + it * 64;
+    if (c < n_chunks) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) { float dlt = v[it][j] - mean; sq += dlt * dlt; }
+    }
+  }
+  float rstd = rsqrtf(wave_sum(sq) / (float)hidden + eps);
+  bf16_t* orow = out + (int64_t)r * hidden;
+#pragma unroll
+  for (int it = 0; it < ITERS; ++it) {
+    int c = lane + it * 64;
+    if (c < n_chunks) {
+      float g8[8], b8[8], o8[8];
+      ResidIO<bf16_t>::load8(gain + c * 8, g8);
+      ResidIO<bf16_t>::load8(bias + c * 8, b8);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) o8[j] = (v[it][j] - mean) * rstd * g8[j] + b8[j];
+      ResidIO<bf16_t>::store8(orow + c * 8, o8);
+    }
+  }
+}
+
+template <typename XT>
+static hipError_t gather_ln_dispatch(const void* x, const bf16_t* add, const int32_t* rows, int n_rows,
+                                     int hidden, const bf16_t* gain, const bf16_t* bias, float eps,
+                                     bf16_t* out, hipStream_t st) {
+  int iters = (hidden / 8 + 63) / 64;
+  dim3 grid((n_rows + 3) / 4), block(256);
+  const XT* xp = static_cast<const XT*>(x);
+#define LAUNCH(I)                                                                                   \
+  hipLaunchKernelGGL((gather_ln_kernel<XT, I>), grid, block, 0, st, xp, add, rows, n_rows, hidden, \
+                     gain, bias, eps, out)
+  if (iters <= 1) LAUNCH(1);
+  else if (iters <= 2) LAUNCH(2);
+  else if (iters <= 4) LAUNCH(4);
+  else if (iters <= 8) LAUNCH(8);
+  else LAUNCH(16);
+#undef LAUNCH
+  return hipGetLastError();
+}
+
+hipError_t launch_gather_ln(const void* x, bool x_fp32, const bf16_t* add, const int32_t* rows, int n_rows,
+                            int hidden, const bf16_t* gain, const bf16_t* bias, float eps, bf16_t* out,
+                            hipStream_t st) {
+  if (n_rows <= 0) return hipSuccess;
+  return x_fp32 ? gather_ln_dispatch<float>(x, add, rows, n_rows, hidden, gain, bias, eps, out, st)
+                : gather_ln_dispatch<bf16_t>(x, add, rows, n_rows, hidden, gain, bias, eps, out, st);
+}
+
+// ---------------------------------------------------------------------------------
+// x += s_cur + (s_cur - s_prev) * alpha   (s_prev == nullptr: x += s_cur)
+// ---------------------------------------------------------------------------------
+template <typename XT, bool HAS_PREV>
+__global__ __launch_bounds__(256) void axpy_features_kernel(
+    XT* __restrict__ x, const bf16_t* __restrict__ s_cur, const bf16_t* __restrict__ s_prev,
+    float alpha, int64_t n_chunks) {
+  int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; c < n_chunks; c += stride) {
+    float xv[8], cv[8];
+    ResidIO<XT>::load8(x + c * 8, xv);
+    ResidIO<bf16_t>::load8(s_cur + c * 8, cv);
+    if (HAS_PREV) {
+      float pv[8];
+      ResidIO<bf16_t>::load8(s_prev + c * 8, pv);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) xv[j] += cv[j] + (cv[j] - pv[j]) * alpha;
+    } else {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) xv[j] += cv[j];
+    }
+    ResidIO<XT>::store8(x + c * 8, xv);
+  }
+}
+
+hipError_t launch_axpy_features(void* x, bool x_fp32, const bf16_t* s_cur, const bf16_t* s_prev, float alpha,
+                                int64_t n_elems, hipStream_t st) {
+  int64_t n_chunks = n_elems / 8;
+  if (n_chunks <= 0) return hipSuccess;
+  int64_t want = (n_chunks + 255) / 256;
+  int blocks = (int)(want < 256 * 32 ? want : 256 * 32);
+  dim3 grid(blocks), block(256);
+#define LAUNCH(XT, HP)                                                                       \
+  hipLaunchKernelGGL((axpy_features_kernel<XT, HP>), grid, block, 0, st, static_cast<XT*>(x), \
+                     s_cur, s_prev, alpha, n_chunks)
+  if (x_fp32) { if (s_prev) LAUNCH(float, true); else LAUNCH(float, false); }
+  else        { if (s_prev) LAUNCH(bf16_t, true); else LAUNCH(bf16_t, false); }
+#undef LAUNCH
+  return hipGetLastError();
+}

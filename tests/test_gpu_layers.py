@@ -1,0 +1,242 @@
+"""GPU parity of the layer operations and the step schedule against the CPU oracle.
+
+Each hero_* call is compared with the oracle's matching call on identical seeded,
+bf16-representable inputs: selection indices and ages bit-exact, activations and
+caches within max-abs 2e-2 / mean-relative 5e-3.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import hero_oracle as O
+from paper_2508_17588_amd import binding as B
+from workloads import get_config, make_layer_weights, make_tokens, perturb_tokens, euler_update
+from hero_testlib import assert_close, to_host_f64, upload_weights
+
+pytestmark = pytest.mark.gpu
+
+MID = dict(n_layers=2, n_shallow=1, hidden=256, n_heads=4, head_dim=64, ffn_dim=1024,
+           frames=3, height=10, width=15, n_text=26)     # N = 476: ragged against every tile size
+
+
+def say(msg):
+    print(f"[case] {msg}", flush=True)
+
+
+def make(cfg, std, resid_fp32=True):
+    ws = [make_layer_weights(cfg, l, seed=0, std=std, ln_affine_noise=0.1) for l in range(cfg.n_layers)]
+    cache = B.HeroCache(B.make_config(cfg, resid_fp32=resid_fp32))
+    upload_weights(cache, cfg, ws)
+    orc = O.HeroOracle(cfg, ws)
+    return cache, orc
+
+
+def dev_x(x, resid_fp32=True):
+    t = torch.from_numpy(np.asarray(x, np.float32)).cuda()
+    return t if resid_fp32 else t.to(torch.bfloat16)
+
+
+def check_layer_caches(cache, orc, layer, cfg, tag):
+    c = orc.caches[layer]
+    s = to_host_f64(cache.hero_cache_view(layer, B.VIEW_S_CUR))
+    assert_close(s, c.g_attn + c.g_ffn, f"{tag}: S = G_attn + G_ffn")
+    if layer < cfg.n_shallow:
+        assert_close(to_host_f64(cache.hero_cache_view(layer, B.VIEW_K)), c.k, f"{tag}: K")
+        vt = to_host_f64(cache.hero_cache_view(layer, B.VIEW_VT))
+        assert_close(vt[:, :cfg.n_tokens].T, c.v, f"{tag}: V")
+        assert float(np.abs(vt[:, cfg.n_tokens:]).max(initial=0.0)) == 0.0      # padding stays zero
+    elif c.g_attn_prev is not None:
+        sp = to_host_f64(cache.hero_cache_view(layer, B.VIEW_S_PREV))
+        assert_close(sp, c.g_attn_prev + c.g_ffn_prev, f"{tag}: S_prev")
+
+
+@pytest.mark.parametrize("base,over,std", [("tiny", {}, 0.08), ("tiny", MID, 0.06)])
+@pytest.mark.parametrize("resid_fp32", [True, False])
+def test_full_then_refresh_then_extrapolate(base, over, std, resid_fp32):
+    cfg = get_config(base, **over)
+    say(f"layers {base} {over} std={std} resid_fp32={resid_fp32}")
+    cache, orc = make(cfg, std, resid_fp32)
+    x0 = make_tokens(cfg, seed=1)
+    # --- full step, both layers (layer 0 shallow, layer 1 deep) ---
+    xd = dev_x(x0, resid_fp32)
+    xo = x0.astype(np.float64)
+    for l in range(2):
+        cache.hero_full_layer(l, xd)
+        xo = orc.full_layer(l, xo)
+        torch.cuda.synchronize()
+        assert_close(to_host_f64(xd), xo, f"full layer {l}: x")
+        check_layer_caches(cache, orc, l, cfg, f"full layer {l}")
+        xd = dev_x(round_x(xo, resid_fp32), resid_fp32)    # both sides continue from the same input
+        xo = to_host_f64(xd)
+    # --- second full step so that the deep layer owns two generations ---
+    x1 = perturb_tokens(x0, seed=2, std=0.1)
+    xd, xo = dev_x(x1, resid_fp32), x1.astype(np.float64)
+    for l in range(2):
+        cache.hero_full_layer(l, xd)
+        xo = orc.full_layer(l, xo)
+        torch.cuda.synchronize()
+        check_layer_caches(cache, orc, l, cfg, f"second full layer {l}")
+        xd = dev_x(round_x(xo, resid_fp32), resid_fp32)
+        xo = to_host_f64(xd)
+    # --- cached step: select, refresh layer 0, extrapolate layer 1 ---
+    x2 = perturb_tokens(x0, seed=3, std=0.1)
+    n_sel = B.hero_num_selected(cache.cfg)
+    idx = torch.empty(n_sel, dtype=torch.int32, device="cuda")
+    for step, k in ((5, 1), (6, 2)):
+        got_n = cache.hero_select(step, idx)
+        want_idx = orc.select(step)
+        torch.cuda.synchronize()
+        assert got_n == len(want_idx)
+        np.testing.assert_array_equal(idx.cpu().numpy(), want_idx)
+        xd, xo = dev_x(x2, resid_fp32), x2.astype(np.float64)
+        cache.hero_refresh_layer(0, xd, idx, n_sel)
+        xo = orc.refresh_layer(0, xo, want_idx)
+        torch.cuda.synchronize()
+        assert_close(to_host_f64(xd), xo, f"refresh k={k}: x")
+        check_layer_caches(cache, orc, 0, cfg, f"refresh k={k}")
+        xd = dev_x(round_x(xo, resid_fp32), resid_fp32)
+        xo = to_host_f64(xd)
+        cache.hero_extrapolate_layer(1, xd, k)
+        xo = orc.extrapolate_layer(1, xo, k)
+        torch.cuda.synchronize()
+        assert_close(to_host_f64(xd), xo, f"extrapolate k={k}: x")
+        check_layer_caches(cache, orc, 1, cfg, f"after extrapolate k={k} (cache untouched)")
+    cache.close()
+
+
+def round_x(x64, resid_fp32):
+    return np.asarray(x64, np.float32)
+
+
+def test_refresh_all_rows_reproduces_full_forward_and_empty_is_reuse():
+    cfg = get_config("tiny", **MID).with_(n_layers=1, n_shallow=1)
+    say("refresh idx = all rows == full forward; n_sel = 0 == reuse")
+    cache, orc = make(cfg, 0.06)
+    x0 = make_tokens(cfg, seed=1)
+    x1 = perturb_tokens(x0, seed=2, std=0.5)
+    xd = dev_x(x0)
+    cache.hero_full_layer(0, xd)                     # stale fill
+    # n_sel = 0: x1 + cached S
+    s_before = to_host_f64(cache.hero_cache_view(0, B.VIEW_S_CUR))
+    xd = dev_x(x1)
+    cache.hero_refresh_layer(0, xd, None, 0)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(to_host_f64(xd), x1.astype(np.float64) + s_before, rtol=0, atol=2e-6)
+    # all rows in a random order
+    perm = np.random.default_rng(0).permutation(cfg.n_tokens).astype(np.int32)
+    xd = dev_x(x1)
+    cache.hero_refresh_layer(0, xd, torch.from_numpy(perm).cuda(), len(perm))
+    torch.cuda.synchronize()
+    y, g_attn, g_ffn, k, v = O.block_forward(x1.astype(np.float64), orc.w[0], cfg.n_heads, cfg.ln_eps)
+    assert_close(to_host_f64(xd), y, "refresh(all rows): x")
+    assert_close(to_host_f64(cache.hero_cache_view(0, B.VIEW_S_CUR)), g_attn + g_ffn, "refresh(all rows): S")
+    assert_close(to_host_f64(cache.hero_cache_view(0, B.VIEW_K)), k, "refresh(all rows): K")
+    assert_close(to_host_f64(cache.hero_cache_view(0, B.VIEW_VT))[:, :cfg.n_tokens].T, v, "refresh(all rows): V")
+    cache.close()
+
+
+def test_refresh_leaves_other_rows_bit_unchanged():
+    cfg = get_config("tiny", **MID).with_(n_layers=1, n_shallow=1)
+    say("refresh locality")
+    cache, orc = make(cfg, 0.06)
+    x0 = make_tokens(cfg, seed=1)
+    cache.hero_full_layer(0, dev_x(x0))
+    torch.cuda.synchronize()
+    before = {w: cache.hero_cache_view(0, w).clone() for w in (B.VIEW_S_CUR, B.VIEW_K, B.VIEW_VT)}
+    rows = np.array([30, 31, 200, 475, 26], np.int32)
+    x1 = x0.copy()
+    x1[rows] *= -1.5
+    cache.hero_refresh_layer(0, dev_x(x1), torch.from_numpy(rows).cuda(), len(rows))
+    torch.cuda.synchronize()
+    rest = np.setdiff1d(np.arange(cfg.n_tokens), rows)
+    s, k, vt = (cache.hero_cache_view(0, w) for w in (B.VIEW_S_CUR, B.VIEW_K, B.VIEW_VT))
+    assert torch.equal(s[rest], before[B.VIEW_S_CUR][rest])
+    assert torch.equal(k[rest], before[B.VIEW_K][rest])
+    assert torch.equal(vt[:, rest], before[B.VIEW_VT][:, rest])
+    assert not torch.equal(k[rows.astype(np.int64)], before[B.VIEW_K][rows.astype(np.int64)])
+    cache.close()
+
+
+def test_state_and_argument_errors_on_device():
+    cfg = get_config("tiny")
+    say("error paths")
+    cache = B.HeroCache(B.make_config(cfg))
+    x = dev_x(make_tokens(cfg, seed=1))
+    idx = torch.zeros(64, dtype=torch.int32, device="cuda")
+
+    def code(fn, *a):
+        with pytest.raises(B.HeroError) as e:
+            fn(*a)
+        return e.value.code
+
+    assert code(cache.hero_full_layer, 0, x) == B.HERO_ERR_STATE              # no weights yet
+    upload_weights(cache, cfg, [make_layer_weights(cfg, l) for l in range(2)])
+    assert code(cache.hero_refresh_layer, 0, x, idx, 64) == B.HERO_ERR_STATE  # not filled
+    assert code(cache.hero_extrapolate_layer, 1, x, 1) == B.HERO_ERR_STATE
+    assert code(cache.hero_step, x, 1) == B.HERO_ERR_STATE                    # cached step first
+    assert code(cache.hero_full_layer, 2, x) == B.HERO_ERR_INVALID_ARG
+    cache.hero_step(x, 0)
+    assert code(cache.hero_refresh_layer, 1, x, idx, 64) == B.HERO_ERR_INVALID_ARG   # deep layer
+    assert code(cache.hero_extrapolate_layer, 0, x, 1) == B.HERO_ERR_INVALID_ARG     # shallow layer
+    assert code(cache.hero_extrapolate_layer, 1, x, 9) == B.HERO_ERR_INVALID_ARG     # k > M
+    assert code(cache.hero_refresh_layer, 0, x, idx, 10 ** 6) == B.HERO_ERR_INVALID_ARG
+    assert code(cache.hero_step, x, 7) == B.HERO_ERR_STATE                    # 7 steps after the last full one
+    assert cache.hero_cache_state() == (1, 0)
+    cache.hero_cache_reset()
+    assert cache.hero_cache_state() == (0, -1)
+    assert code(cache.hero_step, x, 1) == B.HERO_ERR_STATE
+    torch.cuda.synchronize()
+    cache.close()
+
+
+def run_schedule(cfg, std, n_steps, check_every_step=True):
+    cache, orc = make(cfg, std)
+    x0 = make_tokens(cfg, seed=1)
+    text0_np = x0[:cfg.n_text].astype(np.float64)
+    xo = x0.astype(np.float64)
+    xd = dev_x(x0)
+    text0_d = xd[:cfg.n_text].clone()
+    worst = (0.0, 0.0)
+    for step in range(n_steps):
+        say(f"  step {step}")
+        x_in_d = xd.clone()
+        cache.hero_step(xd, step)
+        yo = orc.step(xo, step)
+        torch.cuda.synchronize()
+        ma, mr = assert_close(to_host_f64(xd), yo, f"step {step}: x")
+        worst = (max(worst[0], ma), max(worst[1], mr))
+        assert cache.hero_cache_state() == (orc.n_full, orc.last_full)
+        np.testing.assert_array_equal(cache.hero_cache_view(0, B.VIEW_AGES).cpu().numpy(), orc.ages)
+        if orc.last_idx is not None:
+            np.testing.assert_array_equal(cache.hero_cache_view(0, B.VIEW_IDX).cpu().numpy(), orc.last_idx)
+        if check_every_step or step == n_steps - 1:
+            for l in range(cfg.n_layers):
+                check_layer_caches(cache, orc, l, cfg, f"step {step} layer {l}")
+        # toy sampler update, the same on both sides; the GPU side keeps its own trajectory
+        xd = euler_update(x_in_d, xd, text0_d, cfg.n_text, n_steps)
+        xo = euler_update(xo, yo, text0_np, cfg.n_text, n_steps)
+    cache.close()
+    return worst
+
+
+def test_tiny_dit_ten_steps():
+    """Config 1: 2 blocks (block 0 refresh, block 1 extrapolate), 10 steps, ratio 25 %, M = 4."""
+    cfg = get_config("tiny")
+    say("tiny DiT, 10 steps, weights N(0, 0.02)")
+    run_schedule(cfg, 0.02, cfg.n_steps)
+    say("tiny DiT, 10 steps, weights N(0, 0.08)")
+    run_schedule(cfg, 0.08, cfg.n_steps)
+
+
+def test_reduced_42_layer_schedule():
+    """Same structure as the 42-layer workload (L=42, K=8, M=4) on a small grid, 6 steps."""
+    cfg = get_config("reduced_42l")
+    say("reduced 42-layer DiT, 6 steps")
+    run_schedule(cfg, 0.02, cfg.n_steps, check_every_step=False)
+
+
+def test_special_schedules():
+    say("K = 0 (every layer extrapolated) and K = L (every layer refreshed)")
+    run_schedule(get_config("tiny", n_shallow=0, interval=2), 0.08, 5)
+    run_schedule(get_config("tiny", n_shallow=2, interval=3), 0.08, 5)
+    run_schedule(get_config("tiny", interval=1), 0.08, 3)
