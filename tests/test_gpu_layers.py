@@ -50,7 +50,7 @@ def check_layer_caches(cache, orc, layer, cfg, tag):
         assert_close(sp, c.g_attn_prev + c.g_ffn_prev, f"{tag}: S_prev")
 
 
-@pytest.mark.parametrize("base,over,std", [("tiny", {}, 0.08), ("tiny", MID, 0.06)])
+@pytest.mark.parametrize("base,over,std", [("tiny", {}, 0.05), ("tiny", MID, 0.04)])
 @pytest.mark.parametrize("resid_fp32", [True, False])
 def test_full_then_refresh_then_extrapolate(base, over, std, resid_fp32):
     cfg = get_config(base, **over)
@@ -111,7 +111,7 @@ def round_x(x64, resid_fp32):
 def test_refresh_all_rows_reproduces_full_forward_and_empty_is_reuse():
     cfg = get_config("tiny", **MID).with_(n_layers=1, n_shallow=1)
     say("refresh idx = all rows == full forward; n_sel = 0 == reuse")
-    cache, orc = make(cfg, 0.06)
+    cache, orc = make(cfg, 0.04)
     x0 = make_tokens(cfg, seed=1)
     x1 = perturb_tokens(x0, seed=2, std=0.5)
     xd = dev_x(x0)
@@ -138,7 +138,7 @@ def test_refresh_all_rows_reproduces_full_forward_and_empty_is_reuse():
 def test_refresh_leaves_other_rows_bit_unchanged():
     cfg = get_config("tiny", **MID).with_(n_layers=1, n_shallow=1)
     say("refresh locality")
-    cache, orc = make(cfg, 0.06)
+    cache, orc = make(cfg, 0.04)
     x0 = make_tokens(cfg, seed=1)
     cache.hero_full_layer(0, dev_x(x0))
     torch.cuda.synchronize()
@@ -179,7 +179,10 @@ def test_state_and_argument_errors_on_device():
     assert code(cache.hero_refresh_layer, 1, x, idx, 64) == B.HERO_ERR_INVALID_ARG   # deep layer
     assert code(cache.hero_extrapolate_layer, 0, x, 1) == B.HERO_ERR_INVALID_ARG     # shallow layer
     assert code(cache.hero_extrapolate_layer, 1, x, 9) == B.HERO_ERR_INVALID_ARG     # k > M
-    assert code(cache.hero_refresh_layer, 0, x, idx, 10 ** 6) == B.HERO_ERR_INVALID_ARG
+    import ctypes
+    rc = cache.lib.hero_refresh_layer(cache.handle, 0, ctypes.c_void_p(x.data_ptr()),
+                                      ctypes.c_void_p(idx.data_ptr()), 10 ** 6, None)
+    assert rc == B.HERO_ERR_INVALID_ARG                                       # n_sel > N
     assert code(cache.hero_step, x, 7) == B.HERO_ERR_STATE                    # 7 steps after the last full one
     assert cache.hero_cache_state() == (1, 0)
     cache.hero_cache_reset()
@@ -224,8 +227,8 @@ def test_tiny_dit_ten_steps():
     cfg = get_config("tiny")
     say("tiny DiT, 10 steps, weights N(0, 0.02)")
     run_schedule(cfg, 0.02, cfg.n_steps)
-    say("tiny DiT, 10 steps, weights N(0, 0.08)")
-    run_schedule(cfg, 0.08, cfg.n_steps)
+    say("tiny DiT, 10 steps, weights N(0, 0.05)")
+    run_schedule(cfg, 0.05, cfg.n_steps)
 
 
 def test_reduced_42_layer_schedule():
@@ -237,6 +240,6 @@ def test_reduced_42_layer_schedule():
 
 def test_special_schedules():
     say("K = 0 (every layer extrapolated) and K = L (every layer refreshed)")
-    run_schedule(get_config("tiny", n_shallow=0, interval=2), 0.08, 5)
-    run_schedule(get_config("tiny", n_shallow=2, interval=3), 0.08, 5)
-    run_schedule(get_config("tiny", interval=1), 0.08, 3)
+    run_schedule(get_config("tiny", n_shallow=0, interval=2), 0.05, 5)
+    run_schedule(get_config("tiny", n_shallow=2, interval=3), 0.05, 5)
+    run_schedule(get_config("tiny", interval=1), 0.05, 3)
