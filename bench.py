@@ -1,0 +1,189 @@
+#!/usr/bin/env python3
+"""Benchmark of the cached DiT denoising step (HERO) on one MI355X.
+
+A "step" is one denoising step of the whole hot path -- hero_step over all layers --
+on one synthetic CogVideoX-5B-shaped batch.  The default workload is the 42-layer,
+50-step schedule (first 8 layers patch-wise refresh, the rest linear extrapolation, a
+full recompute every 4th step).  Inputs and weights are seeded synthetic draws that are
+resident in HBM before the timed region starts.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def parse():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=50)
+    p.add_argument("--warmup", type=int, default=2)
+    p.add_argument("--workload", default="cvx5b_42l")
+    p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--cpu-sample-rows", type=int, default=4485)
+    return p.parse_args()
+
+
+def device_weights(cfg, torch, gen):
+    """Seeded N(0, 0.02) bf16 parameters drawn on the device (LayerNorm gain 1, bias 0)."""
+    d, f = cfg.hidden, cfg.ffn_dim
+
+    def draw(*shape):
+        return (torch.randn(*shape, generator=gen, device="cuda", dtype=torch.float32) * 0.02).to(torch.bfloat16)
+
+    return {
+        "ln1_g": torch.ones(d, device="cuda", dtype=torch.bfloat16),
+        "ln1_b": torch.zeros(d, device="cuda", dtype=torch.bfloat16),
+        "w_qkv": draw(3 * d, d), "b_qkv": draw(3 * d), "w_o": draw(d, d), "b_o": draw(d),
+        "ln2_g": torch.ones(d, device="cuda", dtype=torch.bfloat16),
+        "ln2_b": torch.zeros(d, device="cuda", dtype=torch.bfloat16),
+        "w_ff1": draw(f, d), "b_ff1": draw(f), "w_ff2": draw(d, f), "b_ff2": draw(d),
+    }
+
+
+def cpu_baseline(cfg, w0, x0_host, n_rows, n_steps):
+    """Times the CPU oracle (as it stands) on a bounded sample: one refresh-layer call on
+    the first n_rows selected rows of one layer at the real shape, against a synthetic
+    filled cache; scales to ms per denoising step by the FLOPs ratio."""
+    import numpy as np
+    from threadpoolctl import threadpool_info
+    from oracle import hero_oracle as O
+
+    rng = np.random.default_rng(7)
+    n, d = cfg.n_tokens, cfg.hidden
+    w64 = {k: v.astype(np.float64) for k, v in w0.items()}
+    cache = O.LayerCache()
+    cache.k = rng.standard_normal((n, d))
+    cache.v = rng.standard_normal((n, d))
+    cache.g_attn = rng.standard_normal((n, d)) * 0.1
+    cache.g_ffn = rng.standard_normal((n, d)) * 0.1
+    idx, _ = O.select(np.zeros(cfg.n_video, np.int32), cfg, 1)
+    idx = idx[:n_rows]
+    x = x0_host.astype(np.float64)
+    t0 = time.perf_counter()
+    O.refresh_layer(x, w64, cache, idx, cfg.n_heads, cfg.ln_eps)
+    dt = time.perf_counter() - t0
+    sample_flops = O.layer_flops(len(idx), n, d, cfg.ffn_dim)
+    step_flops = O.schedule_flops(cfg, n_steps) / n_steps
+    cores = max([i.get("num_threads", 1) for i in threadpool_info() if i.get("user_api") == "blas"] or [1])
+    return {
+        "value": dt * 1e3 * step_flops / sample_flops, "unit": "ms per denoising step (extrapolated by FLOPs)",
+        "cores": cores, "kind": "oracle",
+        "sample": f"oracle refresh_layer (float64 numpy) on {len(idx)} of the selected rows of one "
+                  f"{cfg.hidden}-wide layer against all {n} cached keys: {dt:.2f} s for "
+                  f"{sample_flops / 1e12:.3f} TFLOP; one mean step of the schedule is {step_flops / 1e12:.1f} TFLOP",
+        "sample_seconds": dt,
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2508_17588_amd import binding as B
+    from workloads import get_config
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    B.load_library()          # fails loudly when the HIP library has not been built
+    cfg = get_config(args.workload)
+    torch.cuda.set_device(0)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(0)
+    cache = B.HeroCache(B.make_config(cfg))
+    weights = []
+    for l in range(cfg.n_layers):
+        w = device_weights(cfg, torch, gen)
+        cache.hero_set_layer_weights(l, w)
+        weights.append(w)
+    gen.manual_seed(1)
+    x0 = torch.randn(cfg.n_tokens, cfg.hidden, generator=gen, device="cuda", dtype=torch.float32)
+    if not cfg.resid_fp32:
+        x0 = x0.to(torch.bfloat16)
+    x = x0.clone()
+    n_sel = B.hero_num_selected(cache.cfg)
+
+    for s in range(args.warmup):
+        x.copy_(x0)
+        cache.hero_step(x, s)
+    torch.cuda.synchronize()
+    cache.hero_cache_reset()
+    torch.cuda.synchronize()
+
+    K = args.steps
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(K + 1)]
+    cache.hero_profile_begin()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev[0].record()
+    for s in range(K):
+        x.copy_(x0)            # every step starts from a latent of the same statistics
+        cache.hero_step(x, s)
+        ev[s + 1].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prof = cache.hero_profile_end()
+    assert bool(torch.isfinite(x).all()), "non-finite activations"
+
+    ms_per_step = (t1 - t0) * 1e3 / K
+    step_ms = [ev[i].elapsed_time(ev[i + 1]) for i in range(K)]
+    full_ms = [t for s, t in enumerate(step_ms) if s % cfg.interval == 0]
+    cached_ms = [t for s, t in enumerate(step_ms) if s % cfg.interval != 0]
+    mean = lambda v: sum(v) / len(v) if v else None
+
+    kernels = {}
+    for name, (ms, cnt, work) in prof.items():
+        kind = name.split("/")[0]
+        mfma = kind.startswith("gemm") or kind == "attention"
+        rate = work / (ms * 1e-3) / (1e12 if mfma else 1e9) if ms > 0 else 0.0
+        kernels[name] = {"total_ms": round(ms, 3), "launches": cnt, "avg_ms": round(ms / cnt, 4),
+                         "achieved": round(rate, 2), "unit": "TFLOP/s" if mfma else "GB/s",
+                         "frac": round(rate / (PEAK_BF16_TFLOPS if mfma else PEAK_HBM_GBS), 4)}
+    dominant = max(kernels, key=lambda k: kernels[k]["total_ms"])
+    dk = kernels[dominant]
+    mfma = dk["unit"] == "TFLOP/s"
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            traffic = json.load(f).get(args.workload, {}).get(dominant)
+    roofline = {"kernel": dominant, "bound": "mfma" if mfma else "hbm", "achieved": dk["achieved"],
+                "peak": PEAK_BF16_TFLOPS if mfma else PEAK_HBM_GBS, "unit": dk["unit"], "frac": dk["frac"],
+                "avg_launch_ms": dk["avg_ms"], "launches": dk["launches"], "traffic": traffic}
+
+    out = {
+        "metric": "ms per denoising step (42-layer DiT)" if cfg.n_layers == 42 else "ms per denoising step",
+        "value": round(ms_per_step, 3), "unit": "ms", "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 3), "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": args.workload, "layers": cfg.n_layers, "shallow_layers": cfg.n_shallow,
+                   "interval": cfg.interval, "hidden": cfg.hidden, "heads": cfg.n_heads, "ffn": cfg.ffn_dim,
+                   "tokens": cfg.n_tokens, "refreshed_rows": n_sel, "resid": "fp32" if cfg.resid_fp32 else "bf16"},
+        "full_step_ms": round(mean(full_ms), 3) if full_ms else None,
+        "cached_step_ms": round(mean(cached_ms), 3) if cached_ms else None,
+        "speedup_vs_all_full": round(mean(full_ms) / ms_per_step, 3) if full_ms else None,
+        "roofline": roofline,
+        "kernels": kernels,
+        "paper_context": "paper reports 1.73x (FLOPs ratio; 1.68x by latency) on A100-80G, Aether, M=2, K=20, R=0.2",
+    }
+    if not args.no_cpu_baseline:
+        w0 = {k: v.float().cpu().numpy() for k, v in weights[0].items()}
+        out["cpu_baseline"] = cpu_baseline(cfg, w0, x0.float().cpu().numpy(), args.cpu_sample_rows, K)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -143,6 +143,21 @@ int hero_cache_view(hero_cache_t c, int32_t layer, int32_t what, void** dev_ptr,
 /* Schedule state: number of full steps taken and the index of the last one (-1 if none). */
 int hero_cache_state(hero_cache_t c, int32_t* n_full, int32_t* last_full_step);
 
+/* ---- per-kernel timing (measurement hook; not part of the method) ------------------
+ * Between hero_profile_begin() and hero_profile_end() every kernel launch made through the
+ * handle is bracketed by HIP events on the launch stream.  hero_profile_end() synchronises
+ * the stream and sums, per slot, the elapsed milliseconds, the number of launches and the
+ * algorithmic work (FLOPs for GEMMs and attention, bytes for the row kernels).
+ * Slot = kind for launches made by hero_full_layer, kind + HERO_PROF_KINDS otherwise.
+ * The three output arrays have 2 * HERO_PROF_KINDS entries (any may be NULL). */
+enum {
+  HERO_PROF_SELECT = 0, HERO_PROF_LN = 1, HERO_PROF_GEMM_QKV = 2, HERO_PROF_ATTN = 3,
+  HERO_PROF_GEMM_O = 4, HERO_PROF_GEMM_FF1 = 5, HERO_PROF_GEMM_FF2 = 6, HERO_PROF_RESID = 7,
+  HERO_PROF_EXTRAP = 8, HERO_PROF_KINDS = 9
+};
+int hero_profile_begin(hero_cache_t c);
+int hero_profile_end(hero_cache_t c, void* stream, double* ms, int64_t* launches, double* work);
+
 /* ---- building blocks, exposed so each kernel can be checked on its own ------------- */
 
 /* out[i,:] = LayerNorm(x[rows[i],:] (+ add[rows[i],:])) * gain + bias, bf16 out [n_rows, hidden].

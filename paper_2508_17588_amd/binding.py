@@ -27,6 +27,8 @@ DTYPE_FP32 = 1
 
 VIEW_S_CUR, VIEW_S_PREV, VIEW_K, VIEW_VT, VIEW_AGES, VIEW_IDX = range(6)
 
+PROF_KINDS = ("select", "ln", "gemm_qkv", "attention", "gemm_o", "gemm_ff1", "gemm_ff2", "resid", "extrap")
+
 WEIGHT_FIELDS = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
                  "ln2_g", "ln2_b", "w_ff1", "b_ff1", "w_ff2", "b_ff2")
 
@@ -34,7 +36,7 @@ EXPORTS = (
     "hero_last_error", "hero_num_selected", "hero_cache_bytes", "hero_cache_create",
     "hero_cache_destroy", "hero_cache_reset", "hero_set_layer_weights", "hero_full_layer",
     "hero_select", "hero_reset_ages", "hero_refresh_layer", "hero_extrapolate_layer", "hero_step",
-    "hero_cache_view", "hero_cache_state", "hero_gather_ln", "hero_linear", "hero_attention",
+    "hero_cache_view", "hero_cache_state", "hero_profile_begin", "hero_profile_end", "hero_gather_ln", "hero_linear", "hero_attention",
     "hero_axpy_features",
 )
 
@@ -87,6 +89,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
         "hero_step": [P, P, I, P],
         "hero_cache_view": [P, I, I, POINTER(c_void_p), POINTER(c_int64)],
         "hero_cache_state": [P, POINTER(c_int32), POINTER(c_int32)],
+        "hero_profile_begin": [P],
+        "hero_profile_end": [P, P, POINTER(ctypes.c_double), POINTER(c_int64), POINTER(ctypes.c_double)],
         "hero_gather_ln": [P, I, P, P, I, I, P, P, c_float, P, P],
         "hero_linear": [P, P, P, P, I, I, I, I, P],
         "hero_attention": [P, P, P, c_int64, P, I, I, I, I, P],
@@ -229,6 +233,21 @@ class HeroCache:
         a, b = c_int32(0), c_int32(0)
         _check(self.lib.hero_cache_state(self.handle, byref(a), byref(b)))
         return a.value, b.value
+
+    def hero_profile_begin(self):
+        _check(self.lib.hero_profile_begin(self.handle))
+
+    def hero_profile_end(self):
+        """-> {slot_name: (ms, launches, work)}; slot names end in '/full' or '/cached'."""
+        n = 2 * len(PROF_KINDS)
+        ms, cnt, work = (ctypes.c_double * n)(), (c_int64 * n)(), (ctypes.c_double * n)()
+        _check(self.lib.hero_profile_end(self.handle, _stream(), ms, cnt, work))
+        out = {}
+        for i in range(n):
+            if cnt[i]:
+                name = PROF_KINDS[i % len(PROF_KINDS)] + ("/full" if i < len(PROF_KINDS) else "/cached")
+                out[name] = (ms[i], cnt[i], work[i])
+        return out
 
     def hero_cache_view(self, layer: int, what: int):
         """Returns a torch tensor aliasing the cache slab (no copy)."""

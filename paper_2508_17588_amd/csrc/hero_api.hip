@@ -130,6 +130,26 @@ Layout make_layout(const hero_config& c) {
   return L;
 }
 
+struct Profiler {
+  struct Rec { int slot; size_t e0, e1; double work; };
+  bool on = false;
+  std::vector<hipEvent_t> pool;
+  size_t used = 0;
+  std::vector<Rec> recs;
+  hipError_t next(hipEvent_t* ev, size_t* id) {
+    if (used == pool.size()) {
+      hipEvent_t e;
+      hipError_t rc = hipEventCreate(&e);
+      if (rc != hipSuccess) return rc;
+      pool.push_back(e);
+    }
+    *id = used;
+    *ev = pool[used++];
+    return hipSuccess;
+  }
+  ~Profiler() { for (hipEvent_t e : pool) (void)hipEventDestroy(e); }
+};
+
 struct LayerState {
   bf16_t* s_cur = nullptr;
   bf16_t* s_prev = nullptr;   // deep only
@@ -155,6 +175,8 @@ struct hero_cache {
   int n_full = 0;
   int last_full = -1;
   int last_n_sel = 0;
+  Profiler prof;
+  bool in_full = false;   // launches come from hero_full_layer (profiling slot selection)
 };
 
 namespace {
@@ -170,6 +192,22 @@ int check_layer(hero_cache_t c, int layer) {
   return HERO_OK;
 }
 
+// Launch `expr` on stream `st`; when profiling is on, bracket it with events.
+#define PROF_LAUNCH(c, kind, work_, st, expr)                                        \
+  do {                                                                               \
+    if ((c)->prof.on) {                                                              \
+      hipEvent_t e0_, e1_; size_t i0_, i1_;                                          \
+      HIP_TRY((c)->prof.next(&e0_, &i0_));                                           \
+      HIP_TRY((c)->prof.next(&e1_, &i1_));                                           \
+      HIP_TRY(hipEventRecord(e0_, st));                                              \
+      HIP_TRY(expr);                                                                 \
+      HIP_TRY(hipEventRecord(e1_, st));                                              \
+      (c)->prof.recs.push_back({(kind) + ((c)->in_full ? 0 : HERO_PROF_KINDS), i0_, i1_, (double)(work_)}); \
+    } else {                                                                         \
+      HIP_TRY(expr);                                                                 \
+    }                                                                                \
+  } while (0)
+
 // The block of Eq. 2 on the rows listed in `rows` (nullptr = all N rows), writing K/V to
 // (k_dst, vt_dst) and the branch features to s_dst; ends before the residual add.
 int run_block_rows(hero_cache_t c, LayerState& ls, void* x, const int32_t* rows, int n_rows, bf16_t* k_dst,
@@ -178,36 +216,41 @@ int run_block_rows(hero_cache_t c, LayerState& ls, void* x, const int32_t* rows,
   const bool x_fp32 = cfg.resid_dtype == HERO_DTYPE_FP32;
   const int d = cfg.hidden;
   const hero_layer_weights& w = ls.w;
-  HIP_TRY(launch_gather_ln(x, x_fp32, nullptr, rows, n_rows, d, (const bf16_t*)w.ln1_g, (const bf16_t*)w.ln1_b,
-                           cfg.ln_eps, c->a, st));
+  const double xsz = x_fp32 ? 4.0 : 2.0;
+  const double rd = (double)n_rows * d;
+  const double n_all = (double)c->lay.n_tokens;
+  PROF_LAUNCH(c, HERO_PROF_LN, rd * (xsz + 2.0), st,
+              launch_gather_ln(x, x_fp32, nullptr, rows, n_rows, d, (const bf16_t*)w.ln1_g,
+                               (const bf16_t*)w.ln1_b, cfg.ln_eps, c->a, st));
   GemmArgs g;
   memset(&g, 0, sizeof(g));
   g.a = c->a; g.w = (const bf16_t*)w.w_qkv; g.bias = (const bf16_t*)w.b_qkv;
   g.m = n_rows; g.n = 3 * d; g.k = d; g.epilogue = EPI_QKV; g.rows = rows;
   g.c = c->q; g.k_out = k_dst; g.vt_out = vt_dst; g.ld_vt = c->lay.n_pad; g.d = d;
-  HIP_TRY(launch_gemm(g, st));
+  PROF_LAUNCH(c, HERO_PROF_GEMM_QKV, 6.0 * rd * d, st, launch_gemm(g, st));
 
   AttnArgs at;
   at.q = c->q; at.k = k_dst; at.vt = vt_dst; at.ld_vt = c->lay.n_pad; at.o = c->o;
   at.r = n_rows; at.n_keys = (int)c->lay.n_tokens; at.n_heads = cfg.n_heads; at.head_dim = cfg.head_dim;
-  HIP_TRY(launch_attention(at, st));
+  PROF_LAUNCH(c, HERO_PROF_ATTN, 4.0 * rd * n_all, st, launch_attention(at, st));
 
   memset(&g, 0, sizeof(g));
   g.a = c->o; g.w = (const bf16_t*)w.w_o; g.bias = (const bf16_t*)w.b_o;
   g.m = n_rows; g.n = d; g.k = d; g.epilogue = EPI_SCATTER; g.rows = rows; g.c = s_dst;
-  HIP_TRY(launch_gemm(g, st));
+  PROF_LAUNCH(c, HERO_PROF_GEMM_O, 2.0 * rd * d, st, launch_gemm(g, st));
 
-  HIP_TRY(launch_gather_ln(x, x_fp32, s_dst, rows, n_rows, d, (const bf16_t*)w.ln2_g, (const bf16_t*)w.ln2_b,
-                           cfg.ln_eps, c->a, st));
+  PROF_LAUNCH(c, HERO_PROF_LN, rd * (xsz + 4.0), st,
+              launch_gather_ln(x, x_fp32, s_dst, rows, n_rows, d, (const bf16_t*)w.ln2_g,
+                               (const bf16_t*)w.ln2_b, cfg.ln_eps, c->a, st));
   memset(&g, 0, sizeof(g));
   g.a = c->a; g.w = (const bf16_t*)w.w_ff1; g.bias = (const bf16_t*)w.b_ff1;
   g.m = n_rows; g.n = cfg.ffn_dim; g.k = d; g.epilogue = EPI_GELU; g.c = c->f;
-  HIP_TRY(launch_gemm(g, st));
+  PROF_LAUNCH(c, HERO_PROF_GEMM_FF1, 2.0 * rd * cfg.ffn_dim, st, launch_gemm(g, st));
 
   memset(&g, 0, sizeof(g));
   g.a = c->f; g.w = (const bf16_t*)w.w_ff2; g.bias = (const bf16_t*)w.b_ff2;
   g.m = n_rows; g.n = d; g.k = cfg.ffn_dim; g.epilogue = EPI_SCATTER_ADD; g.rows = rows; g.c = s_dst;
-  HIP_TRY(launch_gemm(g, st));
+  PROF_LAUNCH(c, HERO_PROF_GEMM_FF2, 2.0 * rd * cfg.ffn_dim, st, launch_gemm(g, st));
   return HERO_OK;
 }
 
@@ -335,10 +378,18 @@ int hero_full_layer(hero_cache_t c, int32_t layer, void* dev_x, void* stream) {
   if (!shallow && ls.fills > 0) std::swap(ls.s_cur, ls.s_prev);   // G_{t+M} <- G_t (Sec. 3.4)
   bf16_t* k_dst = shallow ? ls.k : c->ktmp;
   bf16_t* vt_dst = shallow ? ls.vt : c->vtmp;
+  c->in_full = true;
   rc = run_block_rows(c, ls, dev_x, nullptr, (int)c->lay.n_tokens, k_dst, vt_dst, ls.s_cur, st);
+  if (rc) { c->in_full = false; return rc; }
+  const bool x_fp32 = c->cfg.resid_dtype == HERO_DTYPE_FP32;
+  const double nd = (double)c->lay.n_tokens * c->cfg.hidden;
+  rc = [&]() -> int {
+    PROF_LAUNCH(c, HERO_PROF_RESID, nd * (x_fp32 ? 10.0 : 6.0), st,
+                launch_axpy_features(dev_x, x_fp32, ls.s_cur, nullptr, 0.f, c->lay.n_tokens * c->cfg.hidden, st));
+    return HERO_OK;
+  }();
+  c->in_full = false;
   if (rc) return rc;
-  HIP_TRY(launch_axpy_features(dev_x, c->cfg.resid_dtype == HERO_DTYPE_FP32, ls.s_cur, nullptr, 0.f,
-                               c->lay.n_tokens * c->cfg.hidden, st));
   ls.fills += 1;
   return HERO_OK;
 }
@@ -350,7 +401,8 @@ int hero_select(hero_cache_t c, int32_t step, int32_t* dev_idx, int32_t* n_sel_h
   uint64_t seed = c->cfg.seed;
   uint32_t s0 = (uint32_t)seed ^ (uint32_t)(seed >> 32);
   uint32_t salt = fmix32_host(s0 + 0x9E3779B9u * ((uint32_t)step + 1u));
-  HIP_TRY(launch_select(c->geom, salt, c->ages, dev_idx, (hipStream_t)stream));
+  PROF_LAUNCH(c, HERO_PROF_SELECT, 8.0 * c->lay.n_video + 4.0 * c->geom.n_sel, (hipStream_t)stream,
+              launch_select(c->geom, salt, c->ages, dev_idx, (hipStream_t)stream));
   if (n_sel_host) *n_sel_host = c->geom.n_sel;
   return HERO_OK;
 }
@@ -374,8 +426,9 @@ int hero_refresh_layer(hero_cache_t c, int32_t layer, void* dev_x, const int32_t
     rc = run_block_rows(c, ls, dev_x, dev_idx, n_sel, ls.k, ls.vt, ls.s_cur, st);
     if (rc) return rc;
   }
-  HIP_TRY(launch_axpy_features(dev_x, c->cfg.resid_dtype == HERO_DTYPE_FP32, ls.s_cur, nullptr, 0.f,
-                               c->lay.n_tokens * c->cfg.hidden, st));
+  const bool x_fp32 = c->cfg.resid_dtype == HERO_DTYPE_FP32;
+  PROF_LAUNCH(c, HERO_PROF_RESID, (double)c->lay.n_tokens * c->cfg.hidden * (x_fp32 ? 10.0 : 6.0), st,
+              launch_axpy_features(dev_x, x_fp32, ls.s_cur, nullptr, 0.f, c->lay.n_tokens * c->cfg.hidden, st));
   return HERO_OK;
 }
 
@@ -392,8 +445,12 @@ int hero_extrapolate_layer(hero_cache_t c, int32_t layer, void* dev_x, int32_t k
   if (ls.fills == 0) return fail(HERO_ERR_STATE, "layer %d extrapolated before a full step filled its cache", layer);
   const bf16_t* prev = ls.fills >= 2 ? ls.s_prev : nullptr;
   float alpha = (float)k / (float)c->cfg.interval;
-  HIP_TRY(launch_axpy_features(dev_x, c->cfg.resid_dtype == HERO_DTYPE_FP32, ls.s_cur, prev, alpha,
-                               c->lay.n_tokens * c->cfg.hidden, (hipStream_t)stream));
+  const bool x_fp32 = c->cfg.resid_dtype == HERO_DTYPE_FP32;
+  // algorithmic bytes: x in, x out, S_t and (when it exists) S_{t+M}
+  const double bytes = (double)c->lay.n_tokens * c->cfg.hidden * ((x_fp32 ? 8.0 : 4.0) + (prev ? 4.0 : 2.0));
+  PROF_LAUNCH(c, HERO_PROF_EXTRAP, bytes, (hipStream_t)stream,
+              launch_axpy_features(dev_x, x_fp32, ls.s_cur, prev, alpha, c->lay.n_tokens * c->cfg.hidden,
+                                   (hipStream_t)stream));
   return HERO_OK;
 }
 
@@ -449,6 +506,36 @@ int hero_cache_state(hero_cache_t c, int32_t* n_full, int32_t* last_full_step) {
   if (check_handle(c)) return HERO_ERR_INVALID_ARG;
   if (n_full) *n_full = c->n_full;
   if (last_full_step) *last_full_step = c->last_full;
+  return HERO_OK;
+}
+
+int hero_profile_begin(hero_cache_t c) {
+  if (check_handle(c)) return HERO_ERR_INVALID_ARG;
+  c->prof.on = true;
+  c->prof.used = 0;
+  c->prof.recs.clear();
+  return HERO_OK;
+}
+
+int hero_profile_end(hero_cache_t c, void* stream, double* ms, int64_t* launches, double* work) {
+  if (check_handle(c)) return HERO_ERR_INVALID_ARG;
+  if (!c->prof.on) return fail(HERO_ERR_STATE, "hero_profile_end without hero_profile_begin");
+  c->prof.on = false;
+  HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
+  for (int i = 0; i < 2 * HERO_PROF_KINDS; ++i) {
+    if (ms) ms[i] = 0.0;
+    if (launches) launches[i] = 0;
+    if (work) work[i] = 0.0;
+  }
+  for (const Profiler::Rec& r : c->prof.recs) {
+    float t = 0.f;
+    HIP_TRY(hipEventElapsedTime(&t, c->prof.pool[r.e0], c->prof.pool[r.e1]));
+    if (ms) ms[r.slot] += (double)t;
+    if (launches) launches[r.slot] += 1;
+    if (work) work[r.slot] += r.work;
+  }
+  c->prof.recs.clear();
+  c->prof.used = 0;
   return HERO_OK;
 }
 
