@@ -12,7 +12,8 @@
 // B = Q rows held in registers for the whole kernel), so every lane owns one query column:
 // its 32 accumulator values are 32 different keys of the same query, and the row max / row
 // sum of the online softmax are in-lane reductions plus one exchange with lane^32.
-// exp2 is used with the 1/sqrt(hd)*log2(e) scale folded into one FMA.  P^T goes straight
+// exp2 is used with the 1/sqrt(hd)*log2(e) scale folded into one FMA; probabilities are
+// rounded to bf16 by the hardware pack conversion and summed with v_dot2 on the rounded values.  P^T goes straight
 // from the accumulators (rounded to bf16) into the B operand of O^T += V^T P^T: the K rows
 // are read in a permuted order (bits 2 and 3 of the row index swapped) so that the eight
 // k-slots a lane feeds to one PV MFMA are eight consecutive keys, which makes the V^T
@@ -160,39 +161,51 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_kernel(AttnArgs a, int n
     }
 
     // ---- online softmax (per query column), P^T packed to bf16 ----
+    // The running maximum is only raised when some query of the wave exceeds it by more
+    // than 2^8 (the reference point of exp2 is arbitrary as long as O and the row sum use
+    // the same one), so the rescale of O is skipped on most tiles.
     bf16x8_t pf[2][2][2];   // [ig][jb][t]
 #pragma unroll
     for (int ig = 0; ig < 2; ++ig) {
-      float mx = s[0][ig][0];
+      float mx = fmaxf(s[0][ig][0], s[1][ig][0]);
 #pragma unroll
-      for (int jb = 0; jb < 2; ++jb)
+      for (int e = 1; e < 16; e += 1) mx = fmaxf(fmaxf(mx, s[0][ig][e]), s[1][ig][e]);
+      {
+        auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+        mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));   // both halves of the query's keys
+      }
+      const float cand = mx * scale_log2e;
+      if (__builtin_amdgcn_ballot_w64(cand > m_run[ig] + 8.0f) != 0) {
+        const float m_new = fmaxf(m_run[ig], cand);
+        const float alpha = __builtin_amdgcn_exp2f(m_run[ig] - m_new);
+        m_run[ig] = m_new;
+        l_run[ig] *= alpha;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[jb][ig][e]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m_run[ig], mx * scale_log2e);
-      const float alpha = __builtin_amdgcn_exp2f(m_run[ig] - m_new);
-      m_run[ig] = m_new;
-      float psum = 0.f;
+        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) o[cb][ig][e] *= alpha;
+      }
+      const float m_ref = m_run[ig];
+      float psum = l_run[ig];
+      typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+      const bf16x2_t ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
       for (int jb = 0; jb < 2; ++jb) {
         uint32_t pk[8];
 #pragma unroll
         for (int e2 = 0; e2 < 8; ++e2) {
-          float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[jb][ig][2 * e2], scale_log2e, -m_new));
-          float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[jb][ig][2 * e2 + 1], scale_log2e, -m_new));
-          psum += p0 + p1;
-          pk[e2] = pack_bf16x2(p0, p1);
+          float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[jb][ig][2 * e2], scale_log2e, -m_ref));
+          float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[jb][ig][2 * e2 + 1], scale_log2e, -m_ref));
+          pk[e2] = pack_bf16x2_hw(p0, p1);
+          // the row sum uses the rounded probabilities, exactly what multiplies V
+          psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, pk[e2]), ones, psum, false);
         }
         u32x4_t t0 = {pk[0], pk[1], pk[2], pk[3]};
         u32x4_t t1 = {pk[4], pk[5], pk[6], pk[7]};
         pf[ig][jb][0] = *reinterpret_cast<bf16x8_t*>(&t0);
         pf[ig][jb][1] = *reinterpret_cast<bf16x8_t*>(&t1);
       }
-      l_run[ig] = l_run[ig] * alpha + psum;
-#pragma unroll
-      for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) o[cb][ig][e] *= alpha;
+      l_run[ig] = psum;
     }
 
     // ---- O^T += V^T P^T ----
@@ -218,7 +231,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_kernel(AttnArgs a, int n
   // ---- normalise and store: lane owns query column lr, channels 8q + 4lh + e ----
 #pragma unroll
   for (int ig = 0; ig < 2; ++ig) {
-    const float l = l_run[ig] + __shfl_xor(l_run[ig], 32, 64);
+    const float l = l_run[ig] + __shfl_xor(l_run[ig], 32, 64);   // the two key halves of the query
     const float inv = 1.0f / l;
     const int qrow = q0 + ig * 32 + lr;
     if (qrow < a.r) {
@@ -227,8 +240,8 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_kernel(AttnArgs a, int n
       for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-          u32x2_t pk = {pack_bf16x2(o[cb][ig][4 * q] * inv, o[cb][ig][4 * q + 1] * inv),
-                        pack_bf16x2(o[cb][ig][4 * q + 2] * inv, o[cb][ig][4 * q + 3] * inv)};
+          u32x2_t pk = {pack_bf16x2_hw(o[cb][ig][4 * q] * inv, o[cb][ig][4 * q + 1] * inv),
+                        pack_bf16x2_hw(o[cb][ig][4 * q + 2] * inv, o[cb][ig][4 * q + 3] * inv)};
           *reinterpret_cast<u32x2_t*>(op + cb * 32 + 8 * q + 4 * lh) = pk;
         }
     }
