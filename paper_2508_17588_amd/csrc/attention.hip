@@ -3,21 +3,41 @@
 // per head, never materialising the score matrix.
 //
 // Layout: Q [r, H*hd] and K [N, H*hd] row-major, V transposed [H*hd, ld_vt] (key index
-// contiguous), O [r, H*hd].
+// contiguous), O [r, H*hd].  The scores are taken in the base-2 domain: exp2(q_scale * q.k),
+// where the caller either pre-multiplied Q by log2(e)/sqrt(hd) (q_scale = 1) or passes that
+// factor in q_scale.
 //
-// One workgroup = NW waves x 64 queries of one head.  Keys are walked in tiles of 64 staged
+// One workgroup = NW waves x 64 queries of one head; keys are walked in tiles of 64 staged
 // through LDS (K tile [64 keys][hd], V^T tile [hd][64 keys], 16-byte chunks XOR-swizzled so
-// that ds_read_b128 fragment reads are bank-conflict free), double-buffered with register
-// prefetch.  Per tile a wave computes S^T = K Q^T with v_mfma_f32_32x32x16_bf16 (A = K rows,
-// B = Q rows held in registers for the whole kernel), so every lane owns one query column:
-// its 32 accumulator values are 32 different keys of the same query, and the row max / row
-// sum of the online softmax are in-lane reductions plus one exchange with lane^32.
-// exp2 is used with the 1/sqrt(hd)*log2(e) scale folded into one FMA; probabilities are
-// rounded to bf16 by the hardware pack conversion and summed with v_dot2 on the rounded values.  P^T goes straight
-// from the accumulators (rounded to bf16) into the B operand of O^T += V^T P^T: the K rows
-// are read in a permuted order (bits 2 and 3 of the row index swapped) so that the eight
-// k-slots a lane feeds to one PV MFMA are eight consecutive keys, which makes the V^T
+// that ds_read_b128 fragment reads are bank-conflict free).  A wave computes S^T = K Q^T with
+// v_mfma_f32_32x32x16_bf16 (A = K rows, B = Q rows held in registers for the whole kernel),
+// so every lane owns one query column: its accumulator values are different keys of the same
+// query and the softmax reductions are in-lane plus one exchange with lane^32.  P^T goes
+// straight from the accumulators (rounded to bf16) into the B operand of O^T += V^T P^T: the
+// K rows are read in a permuted order (bits 2 and 3 of the row index swapped) so that the
+// eight k-slots a lane feeds to one PV MFMA are eight consecutive keys, which makes the V^T
 // fragment a single 16-byte LDS read.
+//
+// Two code paths share that layout:
+//
+//  * head_dim 64, the production path: a software pipeline over 32-key blocks in which the
+//    QK^T MFMAs of block b+1, the exponentials of block b and the PV MFMAs of block b-1 are
+//    issued together, so the matrix pipe and the VALU/transcendental pipe overlap inside one
+//    wave.  The exponentials are reference-free, p = exp2(s): fp32 and bf16 share an 8-bit
+//    exponent, so no running maximum is needed as long as the scores of a query stay well
+//    inside +-100 (in log2 units), and the softmax is invariant to the reference point.  The
+//    row sum is accumulated in fp32 alongside.  After the last key the row sums are checked:
+//    if any query of the workgroup has a row sum outside [2^-80, 2^80] (or NaN), i.e. its
+//    scores were too large or too small for the reference-free form, the whole workgroup
+//    recomputes its output with the general path below.  K/V tiles go global -> LDS directly
+//    (buffer_load ... lds, 16 bytes per lane) into three rotating buffers, one barrier per
+//    64-key tile; K/V fragments are refilled from LDS half a step before they are used.
+//
+//  * the general path (head_dim 32, and the fallback of the production path): classic online
+//    softmax with a running maximum that is only raised when some query exceeds it by more
+//    than 2^8, one 64-key tile at a time, register-staged double-buffered LDS.
+#include <type_traits>
+
 #include "hero_device.h"
 #include "hero_kernels.h"
 
@@ -25,9 +45,12 @@ namespace {
 
 constexpr int BKV = 64;   // keys per tile
 
+// ------------------------------------------------------------------------------------------
+// general path: online softmax with running maximum; one workgroup = NW waves x 64 queries
+// ------------------------------------------------------------------------------------------
 template <int HD, int NW>
-__global__ __launch_bounds__(NW * 64, 2) void attention_kernel(AttnArgs a, int n_qblocks, int n_blocks,
-                                                               int per_xcd, float scale_log2e) {
+__device__ __forceinline__ void attention_general(const AttnArgs& a, int head, int q0, float scale_log2e,
+                                                  u32x4_t* sK, u32x4_t* sV) {
   constexpr int T = NW * 64;
   constexpr int KCH = HD / 8;             // 16-byte chunks per K-tile row
   constexpr int VCH = BKV / 8;            // 16-byte chunks per V^T-tile row
@@ -36,20 +59,11 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_kernel(AttnArgs a, int n
   constexpr int NKL = BKV * KCH / T;      // K chunks per thread per tile
   constexpr int NVL = HD * VCH / T;       // V^T chunks per thread per tile
   static_assert(BKV * KCH % T == 0 && HD * VCH % T == 0, "tile/threads mismatch");
-  constexpr int K_TILE = BKV * KCH, V_TILE = HD * VCH;   // in 16-byte chunks
+  constexpr int K_TILE = BKV * KCH, V_TILE = HD * VCH;   // in 16-byte chunks; sK, sV hold two tiles each
 
-  // each XCD (consecutive workgroup ids round-robin over 8 XCDs) gets a contiguous range of heads
-  int logical = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
-  if (logical >= n_blocks) return;
-  const int head = logical / n_qblocks, qb = logical % n_qblocks;
   const int d = a.n_heads * HD;
-
-  __shared__ u32x4_t sK[2][K_TILE];
-  __shared__ u32x4_t sV[2][V_TILE];
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
   const int lr = lane & 31, lh = lane >> 5;
-  const int q0 = qb * (NW * 64) + wave * 64;
 
   // Q fragments (B operand): lane holds query q0 + ig*32 + lr, channels 16s + 8*lh .. +7
   bf16x8_t qf[2][KS];
@@ -108,9 +122,9 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_kernel(AttnArgs a, int n
   };
   auto store_tile = [&](int buf) {
 #pragma unroll
-    for (int i = 0; i < NKL; ++i) sK[buf][k_off[i]] = rk[i];
+    for (int i = 0; i < NKL; ++i) sK[buf * K_TILE + k_off[i]] = rk[i];
 #pragma unroll
-    for (int i = 0; i < NVL; ++i) sV[buf][v_off[i]] = rv[i];
+    for (int i = 0; i < NVL; ++i) sV[buf * V_TILE + v_off[i]] = rv[i];
   };
 
   load_tile(0);
@@ -138,7 +152,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_kernel(AttnArgs a, int n
       const int row = jb * 32 + krow_perm;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        u32x4_t t = sK[cur][row * KCH + ((2 * ks + lh) ^ ((row >> 1) & (KCH - 1)))];
+        u32x4_t t = sK[cur * K_TILE + row * KCH + ((2 * ks + lh) ^ ((row >> 1) & (KCH - 1)))];
         bf16x8_t kf = *reinterpret_cast<bf16x8_t*>(&t);
 #pragma unroll
         for (int ig = 0; ig < 2; ++ig)
@@ -187,8 +201,6 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_kernel(AttnArgs a, int n
       }
       const float m_ref = m_run[ig];
       float psum = l_run[ig];
-      typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-      const bf16x2_t ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
       for (int jb = 0; jb < 2; ++jb) {
         uint32_t pk[8];
@@ -197,8 +209,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_kernel(AttnArgs a, int n
           float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[jb][ig][2 * e2], scale_log2e, -m_ref));
           float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[jb][ig][2 * e2 + 1], scale_log2e, -m_ref));
           pk[e2] = pack_bf16x2_hw(p0, p1);
-          // the row sum uses the rounded probabilities, exactly what multiplies V
-          psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, pk[e2]), ones, psum, false);
+          psum += p0 + p1;
         }
         u32x4_t t0 = {pk[0], pk[1], pk[2], pk[3]};
         u32x4_t t1 = {pk[4], pk[5], pk[6], pk[7]};
@@ -216,7 +227,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_kernel(AttnArgs a, int n
       for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-          u32x4_t tv = sV[cur][row * VCH + ((4 * jb + 2 * t + lh) ^ ((row >> 1) & (VCH - 1)))];
+          u32x4_t tv = sV[cur * V_TILE + row * VCH + ((4 * jb + 2 * t + lh) ^ ((row >> 1) & (VCH - 1)))];
           bf16x8_t vf = *reinterpret_cast<bf16x8_t*>(&tv);
 #pragma unroll
           for (int ig = 0; ig < 2; ++ig)
@@ -249,13 +260,342 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_kernel(AttnArgs a, int n
 }
 
 template <int HD, int NW>
+__global__ __launch_bounds__(NW * 64, 2) void attention_general_kernel(AttnArgs a, int n_qblocks, int n_blocks,
+                                                                       int per_xcd) {
+  // each XCD (consecutive workgroup ids round-robin over 8 XCDs) gets a contiguous range of heads
+  int logical = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  if (logical >= n_blocks) return;
+  const int head = logical / n_qblocks, qb = logical % n_qblocks;
+  __shared__ u32x4_t sK[2 * BKV * HD / 8];
+  __shared__ u32x4_t sV[2 * HD * BKV / 8];
+  attention_general<HD, NW>(a, head, qb * (NW * 64) + (threadIdx.x >> 6) * 64, a.q_scale, sK, sV);
+}
+
+// ------------------------------------------------------------------------------------------
+// head_dim 64: pipelined, reference-free exponentials, general path as fallback
+// ------------------------------------------------------------------------------------------
+constexpr int TILE = 512;   // 16-byte chunks per 64-key K or V^T tile at head_dim 64
+
+template <int I> using IC = std::integral_constant<int, I>;
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
+// buffer resource words: base address, no stride, byte count, raw 32-bit data format
+__device__ __forceinline__ u32x4_t make_rsrc_words(const void* p, uint32_t bytes) {
+  const uint64_t addr = (uint64_t)p;
+  u32x4_t r = {(uint32_t)addr, (uint32_t)(addr >> 32) & 0xffffu, bytes, 0x00020000u};
+  r[0] = __builtin_amdgcn_readfirstlane(r[0]); r[1] = __builtin_amdgcn_readfirstlane(r[1]);
+  r[2] = __builtin_amdgcn_readfirstlane(r[2]); r[3] = __builtin_amdgcn_readfirstlane(r[3]);
+  return r;
+}
+
+// 16 bytes per lane from a buffer straight into LDS at lds_base + 16*lane; bytes past the end
+// of the buffer arrive as zero.  The compiler's own builtin for this instruction makes every
+// later LDS read wait for the load, so it is issued by hand and waited for explicitly with
+// vmcnt(0) before the barrier that publishes the tile.  Nothing else in this kernel uses m0.
+__device__ __forceinline__ void direct_lds_load(u32x4_t rsrc, uint32_t lds_base, uint32_t voffset) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+               :: "s"(lds_base), "v"(voffset), "s"(rsrc) : "memory");
+}
+
+template <int NW>
+__global__ __launch_bounds__(NW * 64, 2) void attention_hd64_kernel(AttnArgs a, int n_qblocks, int n_blocks,
+                                                                    int per_xcd) {
+  constexpr int HD = 64;
+  constexpr int NL = 8 / NW;              // 1 KB wave-loads per wave per tile (K and V^T each)
+  static_assert(8 % NW == 0, "waves must divide the 8 wave-loads of a tile");
+
+  int logical = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  if (logical >= n_blocks) return;
+  const int head = logical / n_qblocks, qb = logical % n_qblocks;
+  const int d = a.n_heads * HD;
+
+  __shared__ u32x4_t sK[3][TILE];
+  __shared__ u32x4_t sV[3][TILE];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lr = lane & 31, lh = lane >> 5;
+  const int q0 = qb * (NW * 64) + wave * 64;
+
+  // Q fragments (B operand): lane holds query q0 + ig*32 + lr, channels 16s + 8*lh .. +7
+  bf16x8_t qf[2][4];
+#pragma unroll
+  for (int ig = 0; ig < 2; ++ig) {
+    int qrow = min(q0 + ig * 32 + lr, a.r - 1);
+    const u32x4_t* qp = reinterpret_cast<const u32x4_t*>(a.q + (int64_t)qrow * d + head * HD);
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      u32x4_t t = qp[2 * s + lh];
+      if (a.q_scale != 1.0f) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) t[i] = pack_bf16x2_hw(unpack_lo(t[i]) * a.q_scale, unpack_hi(t[i]) * a.q_scale);
+      }
+      qf[ig][s] = *reinterpret_cast<bf16x8_t*>(&t);
+    }
+  }
+
+  // ---- staging: wave-load j (of 8) fills tile rows 8j..8j+7; lane l -> row 8j + l/8 and LDS
+  //      chunk slot l%8, which holds the row's logical chunk (l%8) ^ ((row>>1)&7) ----
+  const uint32_t k_bytes = (uint32_t)((int64_t)a.n_keys * d * 2 - head * HD * 2);
+  const uint32_t v_bytes = (uint32_t)(((int64_t)d - head * HD) * a.ld_vt * 2);
+  const u32x4_t rsK = make_rsrc_words(a.k + head * HD, k_bytes);
+  const u32x4_t rsV = make_rsrc_words(a.vt + (int64_t)head * HD * a.ld_vt, v_bytes);
+  // LDS byte address of this wave's first 1 KB slot in buffer 0 (wave-uniform)
+  const uint32_t lds_k0 = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)(lds_ptr_t)&sK[0][64 * wave]);
+  const uint32_t lds_v0 = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)(lds_ptr_t)&sV[0][64 * wave]);
+  uint32_t k_voff[NL], v_voff[NL];
+#pragma unroll
+  for (int i = 0; i < NL; ++i) {
+    const int row = 8 * (wave + NW * i) + (lane >> 3);
+    const int c = (lane & 7) ^ ((row >> 1) & 7);
+    k_voff[i] = (uint32_t)row * (uint32_t)(d * 2) + c * 16;
+    v_voff[i] = (uint32_t)row * (uint32_t)(a.ld_vt * 2) + c * 16;
+  }
+  const uint32_t k_tile_bytes = (uint32_t)(BKV * d * 2), v_tile_bytes = BKV * 2;
+  auto gload_k = [&](int tile, int buf) {
+#pragma unroll
+    for (int i = 0; i < NL; ++i)
+      direct_lds_load(rsK, lds_k0 + (uint32_t)(buf * TILE + 64 * NW * i) * 16, k_voff[i] + (uint32_t)tile * k_tile_bytes);
+  };
+  auto gload_v = [&](int tile, int buf) {
+#pragma unroll
+    for (int i = 0; i < NL; ++i)
+      direct_lds_load(rsV, lds_v0 + (uint32_t)(buf * TILE + 64 * NW * i) * 16, v_voff[i] + (uint32_t)tile * v_tile_bytes);
+  };
+
+  // ---- fragment read offsets (chunks) ----
+  const int kperm = (lr & ~12) | ((lr & 4) << 1) | ((lr & 8) >> 1);   // K row read as MFMA row lr
+  int k_fo[4], v_fo[4];
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    k_fo[s] = kperm * 8 + ((2 * s + lh) ^ ((kperm >> 1) & 7));   // + jb*256
+    v_fo[s] = lr * 8 + ((2 * s + lh) ^ ((lr >> 1) & 7));         // index 2*jb + t; + cb*256
+  }
+
+  floatx16_t o[2][2];              // [cb][ig]
+#pragma unroll
+  for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+    for (int ig = 0; ig < 2; ++ig)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) o[cb][ig][e] = 0.f;
+  float la[2] = {0.f, 0.f}, lb[2] = {0.f, 0.f};   // two partial row sums per query group
+
+  floatx16_t s0[2], s1[2];         // scores of the even / odd 32-key block, [ig]
+  bf16x8_t p0[2][2], p1[2][2];     // their probabilities as PV operands, [ig][t]
+  bf16x8_t kfr[4], vfr[4];         // K fragments [ks] and V^T fragments [2*cb + t] of the block in flight
+
+  auto read_k = [&](int kb, int jb) {
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      u32x4_t t = sK[kb][jb * 256 + k_fo[ks]];
+      kfr[ks] = *reinterpret_cast<bf16x8_t*>(&t);
+    }
+  };
+  auto read_v = [&](int vb, int jb) {
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        u32x4_t tv = sV[vb][cb * 256 + v_fo[2 * jb + t]];
+        vfr[2 * cb + t] = *reinterpret_cast<bf16x8_t*>(&tv);
+      }
+  };
+  auto qk = [&](floatx16_t (&sd)[2]) {
+#pragma unroll
+    for (int ig = 0; ig < 2; ++ig)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) sd[ig][e] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+      for (int ig = 0; ig < 2; ++ig)
+        sd[ig] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[ks], qf[ig][ks], sd[ig], 0, 0, 0);
+  };
+  // probabilities of accumulator values 8h .. 8h+7 (the keys of PV k-half t = h)
+  auto sm_half = [&](floatx16_t (&ss)[2], bf16x8_t (&pd)[2][2], int h) {
+#pragma unroll
+    for (int ig = 0; ig < 2; ++ig) {
+      uint32_t pk[4];
+#pragma unroll
+      for (int e2 = 0; e2 < 4; ++e2) {
+        float x0 = __builtin_amdgcn_exp2f(ss[ig][8 * h + 2 * e2]);
+        float x1 = __builtin_amdgcn_exp2f(ss[ig][8 * h + 2 * e2 + 1]);
+        la[ig] += x0;
+        lb[ig] += x1;
+        pk[e2] = pack_bf16x2_hw(x0, x1);
+      }
+      u32x4_t t = {pk[0], pk[1], pk[2], pk[3]};
+      pd[ig][h] = *reinterpret_cast<bf16x8_t*>(&t);
+    }
+  };
+  auto pv = [&](bf16x8_t (&ps)[2][2]) {
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int ig = 0; ig < 2; ++ig)
+          o[cb][ig] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[2 * cb + t], ps[ig][t], o[cb][ig], 0, 0, 0);
+  };
+  // half a step = 8 MFMAs, 16 exponentials, 24 other VALU instructions, 4 fragment reads
+  auto sched_half = [&]() {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);   // MFMA
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // LDS read
+      __builtin_amdgcn_sched_group_barrier(0x400, 4, 0);   // exp
+      __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);   // VALU
+    }
+  };
+
+  const int ntf = a.n_keys / BKV;         // full key tiles; 32-key blocks 0 .. 2*ntf-1
+  if (ntf > 0) {
+    // ---- prologue: scores of blocks 0 and 1, probabilities of block 0 ----
+    gload_k(0, 0); gload_v(0, 0); gload_k(1, 1); gload_v(1, 1); gload_k(2, 2);
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    read_k(0, 0);
+    qk(s0);
+    __builtin_amdgcn_sched_barrier(0);
+    read_k(0, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    qk(s1);
+    sm_half(s0, p0, 0);
+    sm_half(s0, p0, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    read_k(1, 0); read_v(0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+
+    // Iteration `tile` (buffer index P = tile % 3): on entry the fragments hold K tile+1 block 0
+    // and V^T tile block 0, s1 the scores of block 2*tile+1, p0 the probabilities of block 2*tile.
+    // K tile t lives in sK[t % 3], V^T tile t in sV[t % 3]; the loads issued here fill the buffers
+    // whose last readers finished before this iteration's barrier, and are first read after the
+    // next one.
+    auto iter = [&](auto PAR, int tile) {
+      constexpr int P = decltype(PAR)::value;
+      constexpr int P1 = (P + 1) % 3, P2 = (P + 2) % 3;
+      __builtin_amdgcn_s_waitcnt(0x0f70);           // vmcnt(0): this wave's LDS fills have landed
+      __syncthreads();
+      gload_k(tile + 3, P); gload_v(tile + 2, P2);
+      __builtin_amdgcn_sched_barrier(0);
+      // scores of block 2*tile+2, probabilities of block 2*tile+1, PV of block 2*tile
+      qk(s0);
+      sm_half(s1, p1, 0);
+      read_k(P1, 1);
+      sched_half();
+      __builtin_amdgcn_sched_barrier(0);
+      pv(p0);
+      sm_half(s1, p1, 1);
+      read_v(P, 1);
+      sched_half();
+      __builtin_amdgcn_sched_barrier(0);
+      // scores of block 2*tile+3, probabilities of block 2*tile+2, PV of block 2*tile+1
+      qk(s1);
+      sm_half(s0, p0, 0);
+      read_k(P2, 0);
+      sched_half();
+      __builtin_amdgcn_sched_barrier(0);
+      pv(p1);
+      sm_half(s0, p0, 1);
+      read_v(P1, 0);
+      sched_half();
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    const int n_iter = ntf - 1;
+    int tile = 0;
+    for (; tile + 3 <= n_iter; tile += 3) {
+      iter(IC<0>{}, tile);
+      iter(IC<1>{}, tile + 1);
+      iter(IC<2>{}, tile + 2);
+    }
+    int rem = 0;
+    if (tile < n_iter) { iter(IC<0>{}, tile); ++tile; rem = 1; }
+    if (tile < n_iter) { iter(IC<1>{}, tile); ++tile; rem = 2; }
+    // ---- drain: tile = ntf-1 in buffer `rem`; the fragments hold its V^T block 0 ----
+    auto drain = [&](auto PAR) {
+      constexpr int P = decltype(PAR)::value;
+      sm_half(s1, p1, 0);
+      sm_half(s1, p1, 1);
+      pv(p0);
+      __builtin_amdgcn_sched_barrier(0);
+      read_v(P, 1);
+      __builtin_amdgcn_sched_barrier(0);
+      pv(p1);
+    };
+    if (rem == 0) drain(IC<0>{}); else if (rem == 1) drain(IC<1>{}); else drain(IC<2>{});
+  }
+
+  // ---- ragged tail: keys ntf*64 .. n_keys-1 (K rows past the end arrive as zero and are masked) ----
+  const int n_tail = a.n_keys - ntf * BKV;
+  if (n_tail > 0) {
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    gload_k(ntf, 0); gload_v(ntf, 0);
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+#pragma unroll
+    for (int jb = 0; jb < 2; ++jb) {
+      read_k(0, jb); read_v(0, jb);
+      qk(s0);
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int j = jb * 32 + 16 * (g >> 1) + 8 * lh + 4 * (g & 1) + e;
+          if (j >= n_tail) { s0[0][4 * g + e] = -INFINITY; s0[1][4 * g + e] = -INFINITY; }
+        }
+      sm_half(s0, p0, 0);
+      sm_half(s0, p0, 1);
+      pv(p0);
+    }
+  }
+
+  __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): no LDS fill of this wave is still in flight
+
+  // ---- row sums; were the scores inside the range of the reference-free form? ----
+  float l[2];
+  int bad = 0;
+#pragma unroll
+  for (int ig = 0; ig < 2; ++ig) {
+    l[ig] = la[ig] + lb[ig];
+    l[ig] += __shfl_xor(l[ig], 32, 64);   // the two key halves of the query
+    bad |= !(l[ig] >= 0x1p-80f && l[ig] <= 0x1p80f);
+  }
+  if (__syncthreads_or(bad)) {
+    attention_general<HD, NW>(a, head, q0, a.q_scale, &sK[0][0], &sV[0][0]);
+    return;
+  }
+
+  // ---- normalise and store: lane owns query column lr, channels 8q + 4lh + e ----
+#pragma unroll
+  for (int ig = 0; ig < 2; ++ig) {
+    const float inv = 1.0f / l[ig];
+    const int qrow = q0 + ig * 32 + lr;
+    if (qrow < a.r) {
+      bf16_t* op = a.o + (int64_t)qrow * d + head * HD;
+#pragma unroll
+      for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          u32x2_t pk = {pack_bf16x2_hw(o[cb][ig][4 * q] * inv, o[cb][ig][4 * q + 1] * inv),
+                        pack_bf16x2_hw(o[cb][ig][4 * q + 2] * inv, o[cb][ig][4 * q + 3] * inv)};
+          *reinterpret_cast<u32x2_t*>(op + cb * 32 + 8 * q + 4 * lh) = pk;
+        }
+    }
+  }
+}
+
+template <int HD, int NW>
 hipError_t launch_cfg(const AttnArgs& a, hipStream_t st) {
   int n_qblocks = (a.r + NW * 64 - 1) / (NW * 64);
   int n_blocks = n_qblocks * a.n_heads;
   int per_xcd = (n_blocks + 7) / 8;
-  float scale_log2e = 1.4426950408889634f / sqrtf((float)HD);
-  hipLaunchKernelGGL((attention_kernel<HD, NW>), dim3(per_xcd * 8), dim3(NW * 64), 0, st, a, n_qblocks,
-                     n_blocks, per_xcd, scale_log2e);
+  if (HD == 64)
+    hipLaunchKernelGGL((attention_hd64_kernel<NW>), dim3(per_xcd * 8), dim3(NW * 64), 0, st, a, n_qblocks, n_blocks,
+                       per_xcd);
+  else
+    hipLaunchKernelGGL((attention_general_kernel<HD, NW>), dim3(per_xcd * 8), dim3(NW * 64), 0, st, a, n_qblocks,
+                       n_blocks, per_xcd);
   return hipGetLastError();
 }
 
@@ -264,6 +604,10 @@ hipError_t launch_cfg(const AttnArgs& a, hipStream_t st) {
 hipError_t launch_attention(const AttnArgs& a, hipStream_t st) {
   if (a.r <= 0 || a.n_keys <= 0) return hipSuccess;
   if (a.ld_vt % 64 != 0 || a.ld_vt < a.n_keys) return hipErrorInvalidValue;
+  // K and V^T are addressed with 32-bit byte offsets
+  if (((int64_t)a.n_keys + 4 * BKV) * a.n_heads * a.head_dim * 2 >= ((int64_t)1 << 32) ||
+      (int64_t)a.n_heads * a.head_dim * a.ld_vt * 2 >= ((int64_t)1 << 32))
+    return hipErrorInvalidValue;
   if (a.head_dim == 64) return launch_cfg<64, 4>(a, st);
   if (a.head_dim == 32) return launch_cfg<32, 4>(a, st);
   return hipErrorInvalidValue;

@@ -259,6 +259,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_kernel(GemmAr
     n_ok[j] = n < g.n;
     bias[j] = n_ok[j] ? bf16_to_f32(g.bias[n]) : 0.f;
   }
+  const float out_scale = (EPI == EPI_QKV && n0 + wn0 < g.d) ? g.q_scale : 1.0f;
   const int ncol = n0 + wn0 + lr - n_shift;
 #pragma unroll
   for (int i = 0; i < MB; ++i) {
@@ -274,6 +275,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_kernel(GemmAr
           for (int j = 0; j < NB; ++j) {
             if (n_ok[j]) {
               float v = acc[i][j][4 * q + e] + bias[j];
+              if (EPI == EPI_QKV) v *= out_scale;
               if (EPI == EPI_GELU) v = gelu_tanh(v);
               if (EPI == EPI_SCATTER_ADD) v += bf16_to_f32(prow[j * 32]);
               prow[j * 32] = f32_to_bf16_hw(v);
@@ -328,6 +330,8 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t st) {
     return hipErrorInvalidValue;
   // large problems: 256x256 tiles, 8 waves of 128x64; small ones: 128x128 tiles, 4 waves of 64x64
   int64_t big_tiles = (int64_t)((g.m + 255) / 256) * ((g.n + 255) / 256);
-  if (big_tiles >= 128) return launch_cfg<256, 256, 128, 128>(g, st);
+  // (a wave's columns must lie inside one of the Q / K / V thirds, so the 128-wide wave tiles need d % 128 == 0)
+  const bool qkv_split_ok = g.epilogue != EPI_QKV || g.d % 128 == 0;
+  if (big_tiles >= 128 && qkv_split_ok) return launch_cfg<256, 256, 128, 128>(g, st);
   return launch_cfg<128, 128, 64, 64>(g, st);
 }

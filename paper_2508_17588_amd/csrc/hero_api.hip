@@ -227,11 +227,14 @@ int run_block_rows(hero_cache_t c, LayerState& ls, void* x, const int32_t* rows,
   g.a = c->a; g.w = (const bf16_t*)w.w_qkv; g.bias = (const bf16_t*)w.b_qkv;
   g.m = n_rows; g.n = 3 * d; g.k = d; g.epilogue = EPI_QKV; g.rows = rows;
   g.c = c->q; g.k_out = k_dst; g.vt_out = vt_dst; g.ld_vt = c->lay.n_pad; g.d = d;
+  // softmax scale and the change to base 2 are folded into Q before its single bf16 rounding
+  g.q_scale = 1.4426950408889634f / sqrtf((float)cfg.head_dim);
   PROF_LAUNCH(c, HERO_PROF_GEMM_QKV, 6.0 * rd * d, st, launch_gemm(g, st));
 
   AttnArgs at;
   at.q = c->q; at.k = k_dst; at.vt = vt_dst; at.ld_vt = c->lay.n_pad; at.o = c->o;
   at.r = n_rows; at.n_keys = (int)c->lay.n_tokens; at.n_heads = cfg.n_heads; at.head_dim = cfg.head_dim;
+  at.q_scale = 1.0f;
   PROF_LAUNCH(c, HERO_PROF_ATTN, 4.0 * rd * n_all, st, launch_attention(at, st));
 
   memset(&g, 0, sizeof(g));
@@ -576,6 +579,7 @@ int hero_attention(const void* dev_q, const void* dev_k, const void* dev_vt, int
   AttnArgs a;
   a.q = (const bf16_t*)dev_q; a.k = (const bf16_t*)dev_k; a.vt = (const bf16_t*)dev_vt; a.ld_vt = ld_vt;
   a.o = (bf16_t*)dev_o; a.r = r; a.n_keys = n_keys; a.n_heads = n_heads; a.head_dim = head_dim;
+  a.q_scale = 1.4426950408889634f / sqrtf((float)head_dim);
   HIP_TRY(launch_attention(a, (hipStream_t)stream));
   return HERO_OK;
 }

@@ -47,6 +47,7 @@ struct GemmArgs {
   bf16_t* vt_out;       // QKV: V^T cache [d, ld_vt]
   int64_t ld_vt;
   int32_t d;            // QKV: hidden
+  float q_scale;        // QKV: the Q third is stored multiplied by this (softmax scale folded into Q)
 };
 
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t st);
@@ -58,6 +59,7 @@ struct AttnArgs {
   int64_t ld_vt;
   bf16_t* o;            // [r, n_heads*head_dim]
   int32_t r, n_keys, n_heads, head_dim;
+  float q_scale;        // scores are exp2(q_scale * q.k): log2(e)/sqrt(head_dim), or 1 if folded into Q
 };
 
 hipError_t launch_attention(const AttnArgs& a, hipStream_t st);

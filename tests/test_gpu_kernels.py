@@ -116,6 +116,11 @@ def vt_padded(v, ld):
     (1, 1, 1, 64, "plain"), (5, 11, 2, 64, "plain"), (64, 64, 1, 64, "plain"), (300, 1000, 3, 64, "plain"),
     (257, 129, 2, 32, "plain"), (70, 272, 4, 32, "plain"), (130, 777, 2, 64, "peaky"),
     (130, 777, 2, 64, "outlier"), (513, 2048, 1, 64, "plain"),
+    # scores far outside the fp32 exponent range of a reference-free exp2: the head_dim-64 kernel
+    # must notice and recompute with the running-maximum form (huge: overflow, allneg: every
+    # probability underflows, onequery: a single query of the workgroup is affected)
+    (130, 777, 2, 64, "huge"), (130, 777, 2, 64, "allneg"), (300, 200, 1, 64, "onequery"),
+    (70, 272, 4, 32, "huge"),
 ])
 def test_attention(r, n_keys, heads, hd, case):
     say(f"attention r={r} n_keys={n_keys} heads={heads} hd={hd} {case}")
@@ -125,6 +130,13 @@ def test_attention(r, n_keys, heads, hd, case):
         q, k = round_to_bf16(q * 4), round_to_bf16(k * 4)
     if case == "outlier":
         k[3] = round_to_bf16(k[3] * 50)
+    if case == "huge":
+        q = round_to_bf16(q * 64)
+    if case == "allneg":
+        k[:, ::hd] = 16.0           # channel 0 of every head: all keys share a large component ...
+        q[:, ::hd] = -128.0         # ... that every query opposes: all scores ~ -2048/sqrt(hd)
+    if case == "onequery":
+        q[77] = round_to_bf16(q[77] * 200)
     ld = (n_keys + 63) // 64 * 64
     o = torch.full((r + 1, d), 3.0, dtype=torch.bfloat16, device="cuda")
     B.hero_attention(to_dev_bf16(q), to_dev_bf16(k), to_dev_bf16(vt_padded(v, ld)), o, n_keys, heads, hd)
