@@ -287,6 +287,377 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_kernel(GemmAr
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// Large problems: 256 x 256 tile, eight waves (two per SIMD) of 128 x 64, K walked in stages of
+// 64 through two LDS slots that are filled by direct global -> LDS loads (16 bytes per lane).
+//
+//  * What bounds this kernel is the rate at which a CU's vector cache can keep cache-line
+//    requests in flight, so every request must be a whole 128-byte line: a wave-wide load
+//    fetches eight rows of 128 bytes (eight consecutive lanes per row).
+//  * Two waves per SIMD: a wave whose load waits for the address unit cannot issue MFMAs
+//    meanwhile; with a second wave on the SIMD the matrix pipe keeps running.  Each wave issues
+//    its eight loads of the next stage in the first quarter of the current one, one per MFMA,
+//    so that the slowest of them has most of a stage to arrive before the barrier needs it.
+//  * LDS layout of a stage: rows of 128 B whose eight 16-byte chunks are XOR-swizzled with
+//    (row/2)%8 (conflict-free ds_read_b128 fragment reads).  A direct load writes lane l to
+//    byte 16*l of its 1 KB block, i.e. row l/8, chunk slot l%8, so the lane fetches the chunk
+//    that belongs in that slot.
+//  * One barrier per stage.  After the barrier of stage t every wave holds the fragments of
+//    the last k-slice of stage t-1 in registers and has no LDS read outstanding, so the loads
+//    of stage t+1 can overwrite the slot of stage t-1 at once; they have the whole stage
+//    (~2000 cycles) to land.  The fragments of the first slice of stage t are read while the
+//    MFMAs of that last slice run, which hides the LDS latency behind the barrier.
+//  * The waves accumulate C^T blocks (operands swapped), so a lane owns one row m and four
+//    consecutive columns n per accumulator quad.  The epilogue adds the bias, applies the
+//    activation, rounds to bf16 and stages the wave's 128 x 64 sub-tile in LDS (8-byte writes,
+//    row stride 136 B), then streams it out in 16-byte pieces, one 128-byte line per row.
+//    Waves in the V third of the QKV projection keep the operands unswapped and stage the
+//    transposed sub-tile, so V^T rows leave the same way.  The accumulating epilogue (FFN2)
+//    stages fp32 in two halves and rounds once after adding the cached row.
+// ------------------------------------------------------------------------------------------
+constexpr int SBK = 64;                       // k elements per stage: one 128-byte line per row
+constexpr int RING = 2;                       // LDS slots
+constexpr int STAGE_BYTES = 256 * SBK * 2;    // one operand, one stage: 32 KB
+constexpr int RING_B_OFF = RING * STAGE_BYTES;               // W ring starts after the A ring
+constexpr int CST = 136;                      // bf16 staging: bytes per 64-column row (+8 pad)
+constexpr int CSTT = 264;                     // bf16 staging of a transposed sub-tile: 128 columns (+8 pad)
+constexpr int CST32 = 264;                    // fp32 staging: bytes per 64-column row (+8 pad)
+constexpr int STAGE_REGION = 128 * CST;       // per-wave staging region (17408 B)
+constexpr int GEMM256_LDS = 8 * STAGE_REGION > 2 * RING * STAGE_BYTES ? 8 * STAGE_REGION : 2 * RING * STAGE_BYTES;
+static_assert(64 * CST32 <= STAGE_REGION && 64 * CSTT <= STAGE_REGION, "half-tile / transposed tile must fit the staging region");
+
+// buffer resource words: base address, no stride, byte count, raw 32-bit data format
+__device__ __forceinline__ u32x4_t rsrc_words(const void* p, uint32_t bytes) {
+  const uint64_t addr = (uint64_t)p;
+  u32x4_t r = {(uint32_t)addr, (uint32_t)(addr >> 32) & 0xffffu, bytes, 0x00020000u};
+  r[0] = __builtin_amdgcn_readfirstlane(r[0]); r[1] = __builtin_amdgcn_readfirstlane(r[1]);
+  r[2] = __builtin_amdgcn_readfirstlane(r[2]); r[3] = __builtin_amdgcn_readfirstlane(r[3]);
+  return r;
+}
+
+// 16 bytes per lane from a buffer straight into LDS at lds_addr + 16*lane.  The bounds check
+// covers voffset only (rows past the end arrive as zero); soffset carries the k advance.  Issued
+// by hand so that the compiler does not make later LDS reads wait for it: completion is awaited
+// explicitly with vmcnt before the stage's barrier.  Nothing else in the kernel uses m0.
+__device__ __forceinline__ void lds_fill(u32x4_t rsrc, uint32_t lds_addr, uint32_t voffset, uint32_t soffset) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+               :: "s"(lds_addr), "v"(voffset), "s"(rsrc), "s"(soffset) : "memory");
+}
+
+// keeps a wave-uniform value in a scalar register and stops the compiler from hoisting the
+// comparisons made with it out of the loop (hoisted, they come back as lane masks that need
+// VALU instructions at every use)
+__device__ __forceinline__ int opaque(int v) {
+  asm volatile("" : "+s"(v));
+  return v;
+}
+
+template <int EPI>
+__global__ __launch_bounds__(512) void gemm256_kernel(GemmArgs g, int tiles_m, int tiles_n, int per_xcd) {
+  // ---- workgroup id -> tile (each XCD owns a contiguous range, walked in groups of row tiles) ----
+  const int n_tiles = tiles_m * tiles_n;
+  int p = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  if (p >= n_tiles) return;
+  const int group = p / (GROUP_M * tiles_n);
+  const int first_m = group * GROUP_M;
+  const int gsize = min(tiles_m - first_m, GROUP_M);
+  const int in_group = p - group * GROUP_M * tiles_n;
+  const int tm = first_m + in_group % gsize, tn = in_group / gsize;
+  const int m0 = tm * 256, n0 = tn * 256;
+
+  extern __shared__ u32x4_t smem[];
+  const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) void*)smem;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // waves w and w+4 share a SIMD
+  const int wm0 = (wave & 1) * 128, wn0 = (wave >> 1) * 64;
+  const int lr = lane & 31, lh = lane >> 5;
+
+  // ---- direct loads: per stage this wave fills A blocks wave+8i and W blocks wave+8i, i = 0..3
+  //      (8 rows each); lane l fetches, for row l/8 of the block, the chunk that belongs in
+  //      LDS chunk slot l%8 ----
+  const uint32_t row_bytes = (uint32_t)g.k * 2u;
+  const u32x4_t rsA = rsrc_words(g.a, (uint32_t)g.m * row_bytes);
+  const u32x4_t rsB = rsrc_words(g.w, (uint32_t)g.n * row_bytes);
+  uint32_t voffA[4], voffB[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int row = (wave + 8 * i) * 8 + (lane >> 3);
+    const int chunk = (lane & 7) ^ ((row >> 1) & 7);
+    voffA[i] = (uint32_t)(m0 + row) * row_bytes + chunk * 16;
+    voffB[i] = (uint32_t)(n0 + row) * row_bytes + chunk * 16;
+  }
+  const uint32_t fillA = lds0 + wave * 1024, fillB = lds0 + RING_B_OFF + wave * 1024;
+  const int n_stages = g.k / SBK;
+  auto fill_one = [&](int slot, int stage, int q) {
+    const uint32_t koff = (uint32_t)stage * (SBK * 2);
+    if (q < 4) lds_fill(rsA, fillA + (uint32_t)slot * STAGE_BYTES + q * 8192, voffA[q], koff);
+    else lds_fill(rsB, fillB + (uint32_t)slot * STAGE_BYTES + (q - 4) * 8192, voffB[q - 4], koff);
+  };
+
+  // ---- fragment reads: row R, k-chunk c of a stage sits at R*128 + (c ^ ((R/2)%8))*16 ----
+  const char* lbase = reinterpret_cast<const char*>(smem);
+  const char* fa_ks[4];
+  const char* fb_ks[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) {
+    const int off = lr * 128 + (((2 * ks + lh) ^ ((lr >> 1) & 7)) * 16);     // wm0, wn0, 32i are multiples of 16 rows
+    fa_ks[ks] = lbase + wm0 * 128 + off;
+    fb_ks[ks] = lbase + RING_B_OFF + wn0 * 128 + off;
+  }
+  auto frag = [&](const char* ks_base, int slot, int i) {
+    u32x4_t t = *reinterpret_cast<const u32x4_t*>(ks_base + slot * STAGE_BYTES + i * 4096);
+    return *reinterpret_cast<bf16x8_t*>(&t);
+  };
+
+  floatx16_t acc[4][2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  // V third of the QKV projection: keep the natural orientation (lanes along n) so that the
+  // staged sub-tile is V^T
+  const bool natural = (EPI == EPI_QKV) && (n0 + wn0 >= 2 * g.d);
+
+  // Main loop.  Fragment set [1] holds the k-slice consumed first in a stage (the last slice of
+  // the previous stage); the four slices of a stage alternate between the sets.
+  auto main_loop = [&](auto NAT) {
+    constexpr bool NATURAL = decltype(NAT)::value;
+    bf16x8_t fa[2][4], fb[2][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      u32x4_t z = {0u, 0u, 0u, 0u};
+      fa[1][i] = *reinterpret_cast<bf16x8_t*>(&z);
+      if (i < 2) fb[1][i] = *reinterpret_cast<bf16x8_t*>(&z);
+    }
+    // order in which the 6 fragments of a slice are read (the MFMAs use them in the same order)
+    auto read_frag = [&](int set, int slot, int ks, int q) {
+      switch (q) {
+        case 0: fa[set][0] = frag(fa_ks[ks], slot, 0); break;
+        case 1: fb[set][0] = frag(fb_ks[ks], slot, 0); break;
+        case 2: fb[set][1] = frag(fb_ks[ks], slot, 1); break;
+        case 3: fa[set][1] = frag(fa_ks[ks], slot, 1); break;
+        case 4: fa[set][2] = frag(fa_ks[ks], slot, 2); break;
+        default: fa[set][3] = frag(fa_ks[ks], slot, 3); break;
+      }
+    };
+    auto mma_one = [&](int set, int x) {
+      const int i = x >> 1, j = x & 1;
+      if (NATURAL) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0);
+      else acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][j], fa[set][i], acc[i][j], 0, 0, 0);
+    };
+    // one stage: slot S holds stage t
+    auto stage = [&](auto SLOT, int t) {
+      constexpr int S = decltype(SLOT)::value;
+      // Own fills of stage t landed, own fragment reads of stage t-1 complete; after the barrier
+      // the same holds for every wave: stage t is readable and the other slot is free.
+      asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+      __builtin_amdgcn_sched_barrier(0);
+      const bool more = t + 1 < n_stages;
+#pragma unroll
+      for (int sl = 0; sl < 4; ++sl) {
+        // MFMAs of slice sl-1 (set (sl+1)&1) while the fragments of slice sl arrive in set sl&1
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+          if (more && sl == 0) fill_one(S ^ 1, t + 1, x);
+          if (x < 6) read_frag(sl & 1, S, sl, x);
+          mma_one((sl + 1) & 1, x);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+    };
+#pragma unroll
+    for (int q = 0; q < 8; ++q) fill_one(0, 0, q);
+    for (int t = 0; t < n_stages; t += 2) {
+      stage(std::integral_constant<int, 0>{}, t);
+      if (t + 1 < n_stages) stage(std::integral_constant<int, 1>{}, t + 1);
+    }
+    // last slice of the last stage
+#pragma unroll
+    for (int x = 0; x < 8; ++x) mma_one(1, x);
+  };
+  if (EPI == EPI_QKV && natural) main_loop(std::true_type{});
+  else main_loop(std::false_type{});
+
+  // ---- epilogue ----
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();                       // every wave is done with the ring
+  char* region = reinterpret_cast<char*>(smem) + wave * STAGE_REGION;
+  const int mw = m0 + wm0, nw = n0 + wn0;            // origin of this wave's sub-tile
+
+  if (EPI == EPI_QKV && natural) {
+    // acc[i][j][4q+e] = C[m = mw + 32i + 8q + 4lh + e][n = nw + 32j + lr]; stage [n][m]
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int n = nw + 32 * j + lr;
+      const float bias = n < g.n ? bf16_to_f32(g.bias[n]) : 0.f;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          u32x2_t pk = {pack_bf16x2_hw(acc[i][j][4 * q] + bias, acc[i][j][4 * q + 1] + bias),
+                        pack_bf16x2_hw(acc[i][j][4 * q + 2] + bias, acc[i][j][4 * q + 3] + bias)};
+          *reinterpret_cast<u32x2_t*>(region + (32 * j + lr) * CSTT + (32 * i + 8 * q + 4 * lh) * 2) = pk;
+        }
+    }
+    // rows of the region are n (64 of them), 16-byte pieces hold 8 consecutive m
+#pragma unroll 4
+    for (int it = 0; it < 16; ++it) {
+      const int nl = it * 4 + (lane >> 4), piece = lane & 15;
+      const u32x2_t lo = *reinterpret_cast<const u32x2_t*>(region + nl * CSTT + piece * 16);
+      const u32x2_t hi = *reinterpret_cast<const u32x2_t*>(region + nl * CSTT + piece * 16 + 8);
+      const int n = nw + nl, m = mw + piece * 8;
+      if (n < g.n && m < g.m) {
+        bf16_t* dst = g.vt_out + (int64_t)(n - 2 * g.d) * g.ld_vt;
+        if (g.rows == nullptr && m + 8 <= g.m) {
+          u32x4_t v = {lo[0], lo[1], hi[0], hi[1]};
+          *reinterpret_cast<u32x4_t*>(dst + m) = v;
+        } else {
+          const uint32_t w4[4] = {lo[0], lo[1], hi[0], hi[1]};
+#pragma unroll
+          for (int e = 0; e < 8; ++e)
+            if (m + e < g.m) {
+              const int64_t col = g.rows ? (int64_t)g.rows[m + e] : (int64_t)(m + e);
+              dst[col] = (bf16_t)(w4[e >> 1] >> ((e & 1) * 16));
+            }
+        }
+      }
+    }
+    return;
+  }
+
+  // acc[i][j][4q+e] = C[m = mw + 32i + lr][n = nw + 32j + 8q + 4lh + e]
+  const float out_scale = (EPI == EPI_QKV && nw < g.d) ? g.q_scale : 1.0f;
+  // destination of element (m, n): base[row(m) * ld + n - n_shift]
+  bf16_t* base = g.c;
+  int ld = g.n, n_shift = 0;
+  bool use_rows = (EPI == EPI_SCATTER || EPI == EPI_SCATTER_ADD) && g.rows != nullptr;
+  if (EPI == EPI_QKV) {
+    ld = g.d;
+    if (nw >= g.d) { base = g.k_out; n_shift = g.d; use_rows = g.rows != nullptr; }
+  }
+  // bias of the lane's columns: [j][q] holds n = nw + 32j + 8q + 4lh .. +3
+  u32x2_t bias4[2][4];
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int n = min(nw + 32 * j + 8 * q + 4 * lh, g.n - 4);     // columns past N are never stored
+      bias4[j][q] = *reinterpret_cast<const u32x2_t*>(g.bias + n);
+    }
+  auto biased = [&](int i, int j, int q, float* v) {
+    v[0] = acc[i][j][4 * q] + unpack_lo(bias4[j][q][0]);
+    v[1] = acc[i][j][4 * q + 1] + unpack_hi(bias4[j][q][0]);
+    v[2] = acc[i][j][4 * q + 2] + unpack_lo(bias4[j][q][1]);
+    v[3] = acc[i][j][4 * q + 3] + unpack_hi(bias4[j][q][1]);
+  };
+
+  if (EPI == EPI_SCATTER_ADD) {
+    // two halves of 64 rows staged in fp32; S[row] += . with one rounding
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+#pragma unroll
+      for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            float v[4];
+            biased(2 * h + ii, j, q, v);
+            char* dst = region + (32 * ii + lr) * CST32 + (32 * j + 8 * q + 4 * lh) * 4;
+            u32x2_t a0 = {__float_as_uint(v[0]), __float_as_uint(v[1])}, a1 = {__float_as_uint(v[2]), __float_as_uint(v[3])};
+            *reinterpret_cast<u32x2_t*>(dst) = a0;
+            *reinterpret_cast<u32x2_t*>(dst + 8) = a1;
+          }
+      // 64 rows x 8 pieces of 8 columns
+#pragma unroll 4
+      for (int it = 0; it < 8; ++it) {
+        const int rl = it * 8 + (lane >> 3), piece = lane & 7;
+        const char* src = region + rl * CST32 + piece * 32;
+        float v[8];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          u32x2_t t = *reinterpret_cast<const u32x2_t*>(src + 8 * e);
+          v[2 * e] = __uint_as_float(t[0]); v[2 * e + 1] = __uint_as_float(t[1]);
+        }
+        const int m = mw + 64 * h + rl, n = nw + piece * 8;
+        if (m < g.m && n < g.n) {
+          const int64_t row = use_rows ? (int64_t)g.rows[m] : (int64_t)m;
+          u32x4_t* d = reinterpret_cast<u32x4_t*>(base + row * ld + n);
+          u32x4_t old = *d, out;
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            out[e] = pack_bf16x2_hw(v[2 * e] + unpack_lo(old[e]), v[2 * e + 1] + unpack_hi(old[e]));
+          *d = out;
+        }
+      }
+    }
+    return;
+  }
+
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        float v[4];
+        biased(i, j, q, v);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          if (EPI == EPI_QKV) v[e] *= out_scale;
+          if (EPI == EPI_GELU) v[e] = gelu_tanh(v[e]);
+        }
+        u32x2_t pk = {pack_bf16x2_hw(v[0], v[1]), pack_bf16x2_hw(v[2], v[3])};
+        *reinterpret_cast<u32x2_t*>(region + (32 * i + lr) * CST + (32 * j + 8 * q + 4 * lh) * 2) = pk;
+      }
+  // 128 rows x 8 pieces of 8 columns: one 128-byte line per row
+#pragma unroll 4
+  for (int it = 0; it < 16; ++it) {
+    const int rl = it * 8 + (lane >> 3), piece = lane & 7;
+    const u32x2_t lo = *reinterpret_cast<const u32x2_t*>(region + rl * CST + piece * 16);
+    const u32x2_t hi = *reinterpret_cast<const u32x2_t*>(region + rl * CST + piece * 16 + 8);
+    const int m = mw + rl, n = nw + piece * 8;
+    if (m < g.m && n < g.n) {
+      const int64_t row = use_rows ? (int64_t)g.rows[m] : (int64_t)m;
+      u32x4_t v = {lo[0], lo[1], hi[0], hi[1]};
+      *reinterpret_cast<u32x4_t*>(base + row * ld + (n - n_shift)) = v;
+    }
+  }
+}
+
+hipError_t launch_gemm256(const GemmArgs& g, hipStream_t st) {
+  int tiles_m = (g.m + 255) / 256, tiles_n = (g.n + 255) / 256;
+  int n_tiles = tiles_m * tiles_n;
+  int per_xcd = (n_tiles + 7) / 8;
+  dim3 grid(per_xcd * 8), block(512);
+#define HERO_GEMM256_LAUNCH(E)                                                                           \
+  do {                                                                                                   \
+    auto kern = gemm256_kernel<E>;                                                                       \
+    static bool attr_set = false;                                                                        \
+    if (!attr_set) {                                                                                     \
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                            \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, GEMM256_LDS);       \
+      if (e != hipSuccess) return e;                                                                     \
+      attr_set = true;                                                                                   \
+    }                                                                                                    \
+    hipLaunchKernelGGL(kern, grid, block, GEMM256_LDS, st, g, tiles_m, tiles_n, per_xcd);                \
+  } while (0)
+  switch (g.epilogue) {
+    case EPI_PLAIN: HERO_GEMM256_LAUNCH(EPI_PLAIN); break;
+    case EPI_GELU: HERO_GEMM256_LAUNCH(EPI_GELU); break;
+    case EPI_QKV: HERO_GEMM256_LAUNCH(EPI_QKV); break;
+    case EPI_SCATTER: HERO_GEMM256_LAUNCH(EPI_SCATTER); break;
+    case EPI_SCATTER_ADD: HERO_GEMM256_LAUNCH(EPI_SCATTER_ADD); break;
+    default: return hipErrorInvalidValue;
+  }
+#undef HERO_GEMM256_LAUNCH
+  return hipGetLastError();
+}
+
 template <int BM, int BN, int WM, int WN>
 hipError_t launch_cfg(const GemmArgs& g, hipStream_t st) {
   constexpr int T = (BM / WM) * (BN / WN) * 64;
@@ -332,6 +703,7 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t st) {
   int64_t big_tiles = (int64_t)((g.m + 255) / 256) * ((g.n + 255) / 256);
   // (a wave's columns must lie inside one of the Q / K / V thirds, so the 128-wide wave tiles need d % 128 == 0)
   const bool qkv_split_ok = g.epilogue != EPI_QKV || g.d % 128 == 0;
+  if (big_tiles >= 128 && qkv_split_ok) return launch_gemm256(g, st);
   if (big_tiles >= 128 && qkv_split_ok) return launch_cfg<256, 256, 128, 128>(g, st);
   return launch_cfg<128, 128, 64, 64>(g, st);
 }
