@@ -503,7 +503,24 @@ __global__ __launch_bounds__(512) void gemm256_kernel(GemmArgs g, int tiles_m, i
           *reinterpret_cast<u32x2_t*>(region + (32 * j + lr) * CSTT + (32 * i + 8 * q + 4 * lh) * 2) = pk;
         }
     }
-    // rows of the region are n (64 of them), 16-byte pieces hold 8 consecutive m
+    if (g.rows != nullptr) {
+      // scattered columns (refresh): lanes run along m, so the 64 two-byte stores of one instruction
+      // fall into the few cache lines of one V^T row that hold the neighbouring selected tokens
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        const int m = mw + 64 * half + lane;
+        const bool m_ok = m < g.m;
+        const int64_t col = m_ok ? (int64_t)g.rows[m] : 0;
+#pragma unroll 8
+        for (int nl = 0; nl < 64; ++nl) {
+          const bf16_t v = *reinterpret_cast<const bf16_t*>(region + nl * CSTT + (64 * half + lane) * 2);
+          const int n = nw + nl;
+          if (m_ok && n < g.n) g.vt_out[(int64_t)(n - 2 * g.d) * g.ld_vt + col] = v;
+        }
+      }
+      return;
+    }
+    // contiguous columns (full layer): rows of the region are n (64 of them), 16-byte pieces hold 8 consecutive m
 #pragma unroll 4
     for (int it = 0; it < 16; ++it) {
       const int nl = it * 4 + (lane >> 4), piece = lane & 15;
@@ -512,17 +529,14 @@ __global__ __launch_bounds__(512) void gemm256_kernel(GemmArgs g, int tiles_m, i
       const int n = nw + nl, m = mw + piece * 8;
       if (n < g.n && m < g.m) {
         bf16_t* dst = g.vt_out + (int64_t)(n - 2 * g.d) * g.ld_vt;
-        if (g.rows == nullptr && m + 8 <= g.m) {
+        if (m + 8 <= g.m) {
           u32x4_t v = {lo[0], lo[1], hi[0], hi[1]};
           *reinterpret_cast<u32x4_t*>(dst + m) = v;
         } else {
           const uint32_t w4[4] = {lo[0], lo[1], hi[0], hi[1]};
 #pragma unroll
           for (int e = 0; e < 8; ++e)
-            if (m + e < g.m) {
-              const int64_t col = g.rows ? (int64_t)g.rows[m + e] : (int64_t)(m + e);
-              dst[col] = (bf16_t)(w4[e >> 1] >> ((e & 1) * 16));
-            }
+            if (m + e < g.m) dst[m + e] = (bf16_t)(w4[e >> 1] >> ((e & 1) * 16));
         }
       }
     }

@@ -169,6 +169,15 @@ hipError_t launch_gather_ln(const void* x, bool x_fp32, const bf16_t* add, const
 // ---------------------------------------------------------------------------------
 // x += s_cur + (s_cur - s_prev) * alpha   (s_prev == nullptr: x += s_cur)
 // ---------------------------------------------------------------------------------
+// The cached features are read once per call and must not push x out of the memory-side
+// cache: consecutive layers of a step update the same x, which then stays resident there while
+// only the feature streams come from HBM.  Hence the non-temporal loads of s_cur / s_prev.
+__device__ __forceinline__ void load8_stream(const bf16_t* p, float* v) {
+  u32x4_t a = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { v[2 * i] = unpack_lo(a[i]); v[2 * i + 1] = unpack_hi(a[i]); }
+}
+
 template <typename XT, bool HAS_PREV>
 __global__ __launch_bounds__(256) void axpy_features_kernel(
     XT* __restrict__ x, const bf16_t* __restrict__ s_cur, const bf16_t* __restrict__ s_prev,
@@ -177,10 +186,10 @@ __global__ __launch_bounds__(256) void axpy_features_kernel(
   for (int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; c < n_chunks; c += stride) {
     float xv[8], cv[8];
     ResidIO<XT>::load8(x + c * 8, xv);
-    ResidIO<bf16_t>::load8(s_cur + c * 8, cv);
+    load8_stream(s_cur + c * 8, cv);
     if (HAS_PREV) {
       float pv[8];
-      ResidIO<bf16_t>::load8(s_prev + c * 8, pv);
+      load8_stream(s_prev + c * 8, pv);
 #pragma unroll
       for (int j = 0; j < 8; ++j) xv[j] += cv[j] + (cv[j] - pv[j]) * alpha;
     } else {
@@ -196,7 +205,7 @@ hipError_t launch_axpy_features(void* x, bool x_fp32, const bf16_t* s_cur, const
   int64_t n_chunks = n_elems / 8;
   if (n_chunks <= 0) return hipSuccess;
   int64_t want = (n_chunks + 255) / 256;
-  int blocks = (int)(want < 256 * 32 ? want : 256 * 32);
+  int blocks = (int)(want < (1 << 20) ? want : (1 << 20));     // one 8-element chunk per thread up to 2^31 elements
   dim3 grid(blocks), block(256);
 #define LAUNCH(XT, HP)                                                                       \
   hipLaunchKernelGGL((axpy_features_kernel<XT, HP>), grid, block, 0, st, static_cast<XT*>(x), \
