@@ -131,7 +131,13 @@ int hero_extrapolate_layer(hero_cache_t c, int32_t layer, void* dev_x, int32_t k
 
 /* Alg. 1 for one denoising step: full step if step % M == 0 (every layer via
  * hero_full_layer, then ages = 0), otherwise select once and run
- * refresh (l < K) / extrapolate (l >= K) with k = step - last full step. */
+ * refresh (l < K) / extrapolate (l >= K) with k = step - last full step.
+ * On a cached step the deep layers only add their extrapolated features to x
+ * (Eq. 5, Alg. 1), so with two or more deep layers hero_step applies them in one
+ * pass: it keeps T = sum over deep layers of S (fp32, one array per full-step
+ * generation, summed once after each full step) and adds
+ * (1 + k/M) T_t - (k/M) T_{t+M}.  The result equals calling
+ * hero_extrapolate_layer for every deep layer up to fp32 summation order. */
 int hero_step(hero_cache_t c, void* dev_x, int32_t step, void* stream);
 
 /* Read-only views into the handle, for tests and tools.  `what`:
@@ -149,11 +155,13 @@ int hero_cache_state(hero_cache_t c, int32_t* n_full, int32_t* last_full_step);
  * the stream and sums, per slot, the elapsed milliseconds, the number of launches and the
  * algorithmic work (FLOPs for GEMMs and attention, bytes for the row kernels).
  * Slot = kind for launches made by hero_full_layer, kind + HERO_PROF_KINDS otherwise.
+ * HERO_PROF_EXTRAP covers both the per-layer update and hero_step's one-pass update of the
+ * whole deep stack; HERO_PROF_DEEPSUM is the once-per-generation summation behind the latter.
  * The three output arrays have 2 * HERO_PROF_KINDS entries (any may be NULL). */
 enum {
   HERO_PROF_SELECT = 0, HERO_PROF_LN = 1, HERO_PROF_GEMM_QKV = 2, HERO_PROF_ATTN = 3,
   HERO_PROF_GEMM_O = 4, HERO_PROF_GEMM_FF1 = 5, HERO_PROF_GEMM_FF2 = 6, HERO_PROF_RESID = 7,
-  HERO_PROF_EXTRAP = 8, HERO_PROF_KINDS = 9
+  HERO_PROF_EXTRAP = 8, HERO_PROF_DEEPSUM = 9, HERO_PROF_KINDS = 10
 };
 int hero_profile_begin(hero_cache_t c);
 int hero_profile_end(hero_cache_t c, void* stream, double* ms, int64_t* launches, double* work);

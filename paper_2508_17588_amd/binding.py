@@ -27,7 +27,7 @@ DTYPE_FP32 = 1
 
 VIEW_S_CUR, VIEW_S_PREV, VIEW_K, VIEW_VT, VIEW_AGES, VIEW_IDX = range(6)
 
-PROF_KINDS = ("select", "ln", "gemm_qkv", "attention", "gemm_o", "gemm_ff1", "gemm_ff2", "resid", "extrap")
+PROF_KINDS = ("select", "ln", "gemm_qkv", "attention", "gemm_o", "gemm_ff1", "gemm_ff2", "resid", "extrap", "deepsum")
 
 WEIGHT_FIELDS = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
                  "ln2_g", "ln2_b", "w_ff1", "b_ff1", "w_ff2", "b_ff2")

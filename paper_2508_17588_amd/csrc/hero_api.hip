@@ -7,6 +7,7 @@
 #include <cstdio>
 #include <cstring>
 #include <new>
+#include <algorithm>
 #include <utility>
 #include <vector>
 
@@ -95,6 +96,7 @@ struct Layout {
   size_t ages_off;
   size_t layer_stride_shallow, layer_stride_deep;
   size_t s_bytes, k_bytes, vt_bytes;
+  size_t t_off[2], t_bytes;      // fp32 sums of the deep layers' features (two generations); 0 bytes if < 2 deep layers
   size_t cache_bytes;
   // workspace
   size_t idx_off, a_off, q_off, o_off, f_off, ktmp_off, vtmp_off, ws_bytes;
@@ -113,6 +115,9 @@ Layout make_layout(const hero_config& c) {
   L.layer_stride_shallow = L.s_bytes + L.k_bytes + L.vt_bytes;
   L.layer_stride_deep = 2 * L.s_bytes;
   off += (size_t)c.n_shallow * L.layer_stride_shallow + (size_t)(c.n_layers - c.n_shallow) * L.layer_stride_deep;
+  L.t_bytes = (c.n_layers - c.n_shallow >= 2) ? align_up((size_t)L.n_tokens * c.hidden * 4, 256) : 0;
+  L.t_off[0] = off; off += L.t_bytes;
+  L.t_off[1] = off; off += L.t_bytes;
   L.cache_bytes = off;
   size_t w = 0;
   L.idx_off = w; w += align_up((size_t)L.n_tokens * 4, 256);
@@ -172,6 +177,11 @@ struct hero_cache {
   int32_t* idx = nullptr;
   bf16_t *a = nullptr, *q = nullptr, *o = nullptr, *f = nullptr, *ktmp = nullptr, *vtmp = nullptr;
   std::vector<LayerState> layers;
+  // deep-stack sums: slot i holds sum_l S_cur^l taken when the deep layers' fill counts were
+  // t_key[i] (t_is_prev[i] false), or the matching previous-generation sum (t_is_prev[i] true)
+  float* t[2] = {nullptr, nullptr};
+  std::vector<int> t_key[2];
+  bool t_is_prev[2] = {false, false};
   int n_full = 0;
   int last_full = -1;
   int last_n_sel = 0;
@@ -257,6 +267,68 @@ int run_block_rows(hero_cache_t c, LayerState& ls, void* x, const int32_t* rows,
   return HERO_OK;
 }
 
+// Sums the listed feature arrays into t (fp32), 48 arrays per launch.
+int sum_feature_arrays(hero_cache_t c, const std::vector<const bf16_t*>& src, float* t, hipStream_t st) {
+  const int64_t n_elems = c->lay.n_tokens * c->cfg.hidden;
+  for (size_t i = 0; i < src.size(); i += 48) {
+    FeatureList fl;
+    fl.n = (int)std::min<size_t>(48, src.size() - i);
+    for (int j = 0; j < fl.n; ++j) fl.p[j] = src[i + j];
+    const double bytes = (double)n_elems * (2.0 * fl.n + (i ? 8.0 : 4.0));
+    PROF_LAUNCH(c, HERO_PROF_DEEPSUM, bytes, st, launch_sum_features(fl, t, i != 0, n_elems, st));
+  }
+  return HERO_OK;
+}
+
+// The deep layers of a cached step in one pass (Eq. 5 summed over l >= K):
+//   x += (1 + k/M) T_cur - (k/M) T_prev,  T_cur = sum_l S_t^l,  T_prev = sum_l (S_{t+M}^l, or S_t^l
+// for a layer that has only one generation, which then contributes no difference).
+// The sums are cached per state of the deep layers' fill counts and recomputed when it changes;
+// the current sum of one generation serves as the previous sum of the next.
+int apply_deep_stack(hero_cache_t c, void* x, int k, hipStream_t st) {
+  const hero_config& cfg = c->cfg;
+  std::vector<int> fills;
+  bool any_prev = false;
+  for (int l = cfg.n_shallow; l < cfg.n_layers; ++l) {
+    if (c->layers[l].fills == 0) return fail(HERO_ERR_STATE, "layer %d extrapolated before a full step filled its cache", l);
+    fills.push_back(c->layers[l].fills);
+    any_prev = any_prev || c->layers[l].fills >= 2;
+  }
+  std::vector<int> fills_before(fills);
+  for (int& f : fills_before) f -= 1;
+  auto is_cur = [&](int i) { return !c->t_is_prev[i] && c->t_key[i] == fills; };
+  auto is_prev = [&](int i) {
+    return (c->t_is_prev[i] && c->t_key[i] == fills) || (!c->t_is_prev[i] && c->t_key[i] == fills_before);
+  };
+  int cur = is_cur(0) ? 0 : is_cur(1) ? 1 : -1;
+  int prev = !any_prev ? -1 : is_prev(0) ? 0 : is_prev(1) ? 1 : -1;
+  int rc;
+  if (cur < 0) {
+    cur = prev == 0 ? 1 : 0;
+    std::vector<const bf16_t*> src;
+    for (int l = cfg.n_shallow; l < cfg.n_layers; ++l) src.push_back(c->layers[l].s_cur);
+    c->t_key[cur].clear();
+    if ((rc = sum_feature_arrays(c, src, c->t[cur], st)) != HERO_OK) return rc;
+    c->t_key[cur] = fills; c->t_is_prev[cur] = false;
+  }
+  if (any_prev && prev < 0) {
+    prev = cur ^ 1;
+    std::vector<const bf16_t*> src;
+    for (int l = cfg.n_shallow; l < cfg.n_layers; ++l)
+      src.push_back(c->layers[l].fills >= 2 ? c->layers[l].s_prev : c->layers[l].s_cur);
+    c->t_key[prev].clear();
+    if ((rc = sum_feature_arrays(c, src, c->t[prev], st)) != HERO_OK) return rc;
+    c->t_key[prev] = fills; c->t_is_prev[prev] = true;
+  }
+  const bool x_fp32 = cfg.resid_dtype == HERO_DTYPE_FP32;
+  const int64_t n_elems = c->lay.n_tokens * cfg.hidden;
+  const float alpha = (float)k / (float)cfg.interval;
+  const double bytes = (double)n_elems * ((x_fp32 ? 8.0 : 4.0) + (any_prev ? 8.0 : 4.0));
+  PROF_LAUNCH(c, HERO_PROF_EXTRAP, bytes, st,
+              launch_apply_sums(x, x_fp32, c->t[cur], any_prev ? c->t[prev] : nullptr, alpha, n_elems, st));
+  return HERO_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -309,6 +381,7 @@ int hero_cache_create(const hero_config* cfg, void* dev_cache, size_t cache_byte
   c->ktmp = (bf16_t*)(c->ws + L.ktmp_off);
   c->vtmp = (bf16_t*)(c->ws + L.vtmp_off);
   c->layers.resize(cfg->n_layers);
+  if (L.t_bytes) { c->t[0] = (float*)(c->cache + L.t_off[0]); c->t[1] = (float*)(c->cache + L.t_off[1]); }
   size_t off = align_up((size_t)L.n_video * 4, 256);
   for (int l = 0; l < cfg->n_layers; ++l) {
     LayerState& ls = c->layers[l];
@@ -348,6 +421,7 @@ int hero_reset_ages(hero_cache_t c, void* stream) {
 int hero_cache_reset(hero_cache_t c, void* stream) {
   if (check_handle(c)) return HERO_ERR_INVALID_ARG;
   for (auto& ls : c->layers) ls.fills = 0;
+  c->t_key[0].clear(); c->t_key[1].clear();
   c->n_full = 0;
   c->last_full = -1;
   c->last_n_sel = 0;
@@ -478,11 +552,11 @@ int hero_step(hero_cache_t c, void* dev_x, int32_t step, void* stream) {
   int32_t n_sel = 0;
   if ((rc = hero_select(c, step, c->idx, &n_sel, stream)) != HERO_OK) return rc;
   c->last_n_sel = n_sel;
-  for (int l = 0; l < cfg.n_layers; ++l) {
-    rc = l < cfg.n_shallow ? hero_refresh_layer(c, l, dev_x, c->idx, n_sel, stream)
-                           : hero_extrapolate_layer(c, l, dev_x, k, stream);
-    if (rc) return rc;
-  }
+  for (int l = 0; l < cfg.n_shallow; ++l)
+    if ((rc = hero_refresh_layer(c, l, dev_x, c->idx, n_sel, stream)) != HERO_OK) return rc;
+  if (cfg.n_layers - cfg.n_shallow >= 2) return apply_deep_stack(c, dev_x, k, (hipStream_t)stream);
+  for (int l = cfg.n_shallow; l < cfg.n_layers; ++l)
+    if ((rc = hero_extrapolate_layer(c, l, dev_x, k, stream)) != HERO_OK) return rc;
   return HERO_OK;
 }
 

@@ -26,6 +26,16 @@ hipError_t launch_gather_ln(const void* x, bool x_fp32, const bf16_t* add, const
 hipError_t launch_axpy_features(void* x, bool x_fp32, const bf16_t* s_cur, const bf16_t* s_prev, float alpha,
                                 int64_t n_elems, hipStream_t st);
 
+// Deep-stack collapse: t = (accumulate ? t : 0) + sum of up to 48 bf16 feature arrays (fp32 result),
+// and x += t_cur + (t_cur - t_prev) * alpha (t_prev may be null: x += t_cur).
+struct FeatureList {
+  const bf16_t* p[48];
+  int32_t n;
+};
+hipError_t launch_sum_features(const FeatureList& fl, float* t, bool accumulate, int64_t n_elems, hipStream_t st);
+hipError_t launch_apply_sums(void* x, bool x_fp32, const float* t_cur, const float* t_prev, float alpha,
+                             int64_t n_elems, hipStream_t st);
+
 // GEMM epilogues: what happens to act(A W^T + bias)
 enum GemmEpilogue {
   EPI_PLAIN = 0,        // C[m, n]                       (ldc = n)

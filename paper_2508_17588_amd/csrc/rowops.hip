@@ -215,3 +215,73 @@ hipError_t launch_axpy_features(void* x, bool x_fp32, const bf16_t* s_cur, const
 #undef LAUNCH
   return hipGetLastError();
 }
+
+// ---------------------------------------------------------------------------------
+// Deep-stack collapse.  On a cached step the deep layers only add to x (Eq. 5 followed by the
+// residual add, Alg. 1), so their sum over layers can be taken once per full-step generation:
+//   T = sum_l S^l  (fp32),   x += (1 + alpha) * T_cur - alpha * T_prev.
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void sum_features_kernel(FeatureList fl, float* __restrict__ t, int accumulate,
+                                                           int64_t n_chunks) {
+  int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= n_chunks) return;
+  float acc[8];
+  if (accumulate) ResidIO<float>::load8(t + c * 8, acc);
+  else {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+  }
+  for (int l = 0; l < fl.n; ++l) {
+    float v[8];
+    load8_stream(fl.p[l] + c * 8, v);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] += v[j];
+  }
+  ResidIO<float>::store8(t + c * 8, acc);
+}
+
+hipError_t launch_sum_features(const FeatureList& fl, float* t, bool accumulate, int64_t n_elems, hipStream_t st) {
+  int64_t n_chunks = n_elems / 8;
+  if (n_chunks <= 0 || fl.n <= 0) return hipSuccess;
+  int64_t blocks = (n_chunks + 255) / 256;
+  if (blocks > (1 << 30)) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(sum_features_kernel, dim3((unsigned)blocks), dim3(256), 0, st, fl, t, accumulate ? 1 : 0, n_chunks);
+  return hipGetLastError();
+}
+
+template <typename XT, bool HAS_PREV>
+__global__ __launch_bounds__(256) void apply_sums_kernel(XT* __restrict__ x, const float* __restrict__ t_cur,
+                                                         const float* __restrict__ t_prev, float alpha,
+                                                         int64_t n_chunks) {
+  int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= n_chunks) return;
+  float xv[8], cv[8];
+  ResidIO<XT>::load8(x + c * 8, xv);
+  ResidIO<float>::load8(t_cur + c * 8, cv);
+  if (HAS_PREV) {
+    float pv[8];
+    ResidIO<float>::load8(t_prev + c * 8, pv);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) xv[j] += cv[j] + (cv[j] - pv[j]) * alpha;
+  } else {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) xv[j] += cv[j];
+  }
+  ResidIO<XT>::store8(x + c * 8, xv);
+}
+
+hipError_t launch_apply_sums(void* x, bool x_fp32, const float* t_cur, const float* t_prev, float alpha,
+                             int64_t n_elems, hipStream_t st) {
+  int64_t n_chunks = n_elems / 8;
+  if (n_chunks <= 0) return hipSuccess;
+  int64_t blocks = (n_chunks + 255) / 256;
+  if (blocks > (1 << 30)) return hipErrorInvalidValue;
+  dim3 grid((unsigned)blocks), block(256);
+#define LAUNCH(XT, HP)                                                                    \
+  hipLaunchKernelGGL((apply_sums_kernel<XT, HP>), grid, block, 0, st, static_cast<XT*>(x), \
+                     t_cur, t_prev, alpha, n_chunks)
+  if (x_fp32) { if (t_prev) LAUNCH(float, true); else LAUNCH(float, false); }
+  else        { if (t_prev) LAUNCH(bf16_t, true); else LAUNCH(bf16_t, false); }
+#undef LAUNCH
+  return hipGetLastError();
+}
