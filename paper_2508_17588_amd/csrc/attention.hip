@@ -309,8 +309,9 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_hd64_kernel(AttnArgs a, 
   const int head = logical / n_qblocks, qb = logical % n_qblocks;
   const int d = a.n_heads * HD;
 
-  __shared__ u32x4_t sK[3][TILE];
-  __shared__ u32x4_t sV[3][TILE];
+  __shared__ u32x4_t skv[2][3][TILE];            // K tiles, then V^T tiles, three rotating buffers each
+  u32x4_t (&sK)[3][TILE] = skv[0];
+  u32x4_t (&sV)[3][TILE] = skv[1];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 31, lh = lane >> 5;
@@ -566,21 +567,34 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_hd64_kernel(AttnArgs a, 
     return;
   }
 
-  // ---- normalise and store: lane owns query column lr, channels 8q + 4lh + e ----
+  // ---- normalise; the wave's 64 x 64 block goes through LDS (the K/V buffers are idle now: every
+  //      wave passed the barrier above after its last fragment read) so that each query's 128-byte
+  //      output row leaves as one full cache line: lane owns query column lr, channels 8q + 4lh + e ----
+  constexpr int OST = 136;                       // staging row stride in bytes (128 + 8: conflict-free 8-byte writes)
+  static_assert(NW * 64 * OST <= (int)sizeof(skv), "output staging must fit the K/V buffers");
+  char* stage = reinterpret_cast<char*>(&skv[0][0][0]) + wave * (64 * OST);
 #pragma unroll
   for (int ig = 0; ig < 2; ++ig) {
     const float inv = 1.0f / l[ig];
-    const int qrow = q0 + ig * 32 + lr;
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        u32x2_t pk = {pack_bf16x2_hw(o[cb][ig][4 * q] * inv, o[cb][ig][4 * q + 1] * inv),
+                      pack_bf16x2_hw(o[cb][ig][4 * q + 2] * inv, o[cb][ig][4 * q + 3] * inv)};
+        *reinterpret_cast<u32x2_t*>(stage + (ig * 32 + lr) * OST + (cb * 32 + 8 * q + 4 * lh) * 2) = pk;
+      }
+  }
+  // 64 rows x 8 pieces of 16 bytes; the wave reads back only what it wrote itself
+#pragma unroll
+  for (int it = 0; it < 8; ++it) {
+    const int row = it * 8 + (lane >> 3), piece = lane & 7;
+    const u32x2_t lo = *reinterpret_cast<const u32x2_t*>(stage + row * OST + piece * 16);
+    const u32x2_t hi = *reinterpret_cast<const u32x2_t*>(stage + row * OST + piece * 16 + 8);
+    const int qrow = q0 + row;
     if (qrow < a.r) {
-      bf16_t* op = a.o + (int64_t)qrow * d + head * HD;
-#pragma unroll
-      for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          u32x2_t pk = {pack_bf16x2_hw(o[cb][ig][4 * q] * inv, o[cb][ig][4 * q + 1] * inv),
-                        pack_bf16x2_hw(o[cb][ig][4 * q + 2] * inv, o[cb][ig][4 * q + 3] * inv)};
-          *reinterpret_cast<u32x2_t*>(op + cb * 32 + 8 * q + 4 * lh) = pk;
-        }
+      u32x4_t v = {lo[0], lo[1], hi[0], hi[1]};
+      *reinterpret_cast<u32x4_t*>(a.o + (int64_t)qrow * d + head * HD + piece * 8) = v;
     }
   }
 }
