@@ -179,6 +179,16 @@ int hero_gather_ln(const void* dev_x, int32_t x_dtype, const void* dev_add_bf16,
 int hero_linear(const void* dev_a, const void* dev_w, const void* dev_bias, void* dev_c,
                 int32_t m, int32_t n, int32_t k, int32_t act, void* stream);
 
+/* The same product, computed the way the layer entry points compute theirs: with device scratch
+ * (caller-owned, 16-byte aligned, any size; 64 MiB lets every problem use it) the tiles of the
+ * last, partly filled round of workgroups are cut along K, their fp32 partial sums pass through
+ * the scratch and a second kernel adds them up and applies bias and activation.  The result
+ * differs from hero_linear's only by the order of the fp32 additions.  Calls that share a
+ * scratch buffer must not overlap. */
+int hero_linear_scratch(const void* dev_a, const void* dev_w, const void* dev_bias, void* dev_c,
+                        int32_t m, int32_t n, int32_t k, int32_t act, void* dev_scratch,
+                        size_t scratch_bytes, void* stream);
+
 /* O[r,hidden] = softmax(Q K^T / sqrt(head_dim)) V per head; Q [r,hidden], K [n_keys,hidden],
  * V given transposed as vt [hidden, ld_vt] with ld_vt >= n_keys, ld_vt % 64 == 0 and
  * columns n_keys..ld_vt-1 finite (zero).  (FullAttn of Eq. 2 for refreshed queries, Eq. 3.) */

@@ -20,6 +20,7 @@
 // the V third of the QKV projection run their MFMAs with the operands swapped, so their
 // accumulators hold the transposed block and V^T rows are written with row-contiguous
 // lanes.
+#include <algorithm>
 #include <type_traits>
 
 #include "hero_device.h"
@@ -352,18 +353,48 @@ __device__ __forceinline__ int opaque(int v) {
   return v;
 }
 
+// Split of the last, partly filled wave of tiles along k.  Tile slots 0 .. full_items-1 are
+// whole work items; every later slot is cut into `split` k-chunks whose fp32 partial sums go to a
+// workspace (one 256 KB block per chunk, in accumulator order: [i][j][quad][thread] float4) and
+// are added up, and sent through the epilogue, by the fix-up kernel.
+struct SplitK {
+  int32_t full_items;   // tile slots computed whole
+  int32_t split;        // k-chunks per remaining tile slot (1: none)
+  float* ws;
+};
+
+// tile slot -> tile origin (each XCD owns a contiguous range of tiles, walked in groups of
+// group_m row tiles); false for the empty slots that pad the range to a multiple of 8
+__device__ __forceinline__ bool tile_origin(int slot, int tiles_m, int tiles_n, int per_xcd, int group_m,
+                                            int& m0, int& n0) {
+  const int p = (slot % 8) * per_xcd + slot / 8;
+  if (p >= tiles_m * tiles_n) return false;
+  const int group = p / (group_m * tiles_n);
+  const int first_m = group * group_m;
+  const int gsize = min(tiles_m - first_m, group_m);
+  const int in_group = p - group * group_m * tiles_n;
+  m0 = (first_m + in_group % gsize) * 256;
+  n0 = (in_group / gsize) * 256;
+  return true;
+}
+
 template <int EPI>
-__global__ __launch_bounds__(512) void gemm256_kernel(GemmArgs g, int tiles_m, int tiles_n, int per_xcd) {
-  // ---- workgroup id -> tile (each XCD owns a contiguous range, walked in groups of row tiles) ----
-  const int n_tiles = tiles_m * tiles_n;
-  int p = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
-  if (p >= n_tiles) return;
-  const int group = p / (GROUP_M * tiles_n);
-  const int first_m = group * GROUP_M;
-  const int gsize = min(tiles_m - first_m, GROUP_M);
-  const int in_group = p - group * GROUP_M * tiles_n;
-  const int tm = first_m + in_group % gsize, tn = in_group / gsize;
-  const int m0 = tm * 256, n0 = tn * 256;
+__device__ __forceinline__ void epilogue256(const GemmArgs& g, floatx16_t (&acc)[4][2], int m0, int n0, int wave,
+                                            int lane, u32x4_t* smem);
+
+template <int EPI>
+__global__ __launch_bounds__(512) void gemm256_kernel(GemmArgs g, int tiles_m, int tiles_n, int per_xcd,
+                                                      int group_m, SplitK sk) {
+  // ---- workgroup id -> tile slot and k-chunk ----
+  int slot = blockIdx.x, chunk = 0, n_chunks = 1;
+  if (slot >= sk.full_items) {
+    const int r = slot - sk.full_items;
+    slot = sk.full_items + r / sk.split;
+    chunk = r - (r / sk.split) * sk.split;
+    n_chunks = sk.split;
+  }
+  int m0, n0;
+  if (!tile_origin(slot, tiles_m, tiles_n, per_xcd, group_m, m0, n0)) return;
 
   extern __shared__ u32x4_t smem[];
   const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) void*)smem;
@@ -389,6 +420,7 @@ __global__ __launch_bounds__(512) void gemm256_kernel(GemmArgs g, int tiles_m, i
   }
   const uint32_t fillA = lds0 + wave * 1024, fillB = lds0 + RING_B_OFF + wave * 1024;
   const int n_stages = g.k / SBK;
+  const int stage_begin = chunk * n_stages / n_chunks, stage_end = (chunk + 1) * n_stages / n_chunks;
   auto fill_one = [&](int slot, int stage, int q) {
     const uint32_t koff = (uint32_t)stage * (SBK * 2);
     if (q < 4) lds_fill(rsA, fillA + (uint32_t)slot * STAGE_BYTES + q * 8192, voffA[q], koff);
@@ -456,7 +488,7 @@ __global__ __launch_bounds__(512) void gemm256_kernel(GemmArgs g, int tiles_m, i
       // the same holds for every wave: stage t is readable and the other slot is free.
       asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
       __builtin_amdgcn_sched_barrier(0);
-      const bool more = t + 1 < n_stages;
+      const bool more = t + 1 < stage_end;
 #pragma unroll
       for (int sl = 0; sl < 4; ++sl) {
         // MFMAs of slice sl-1 (set (sl+1)&1) while the fragments of slice sl arrive in set sl&1
@@ -470,10 +502,10 @@ __global__ __launch_bounds__(512) void gemm256_kernel(GemmArgs g, int tiles_m, i
       }
     };
 #pragma unroll
-    for (int q = 0; q < 8; ++q) fill_one(0, 0, q);
-    for (int t = 0; t < n_stages; t += 2) {
+    for (int q = 0; q < 8; ++q) fill_one(0, stage_begin, q);
+    for (int t = stage_begin; t < stage_end; t += 2) {
       stage(std::integral_constant<int, 0>{}, t);
-      if (t + 1 < n_stages) stage(std::integral_constant<int, 1>{}, t + 1);
+      if (t + 1 < stage_end) stage(std::integral_constant<int, 1>{}, t + 1);
     }
     // last slice of the last stage
 #pragma unroll
@@ -482,9 +514,59 @@ __global__ __launch_bounds__(512) void gemm256_kernel(GemmArgs g, int tiles_m, i
   if (EPI == EPI_QKV && natural) main_loop(std::true_type{});
   else main_loop(std::false_type{});
 
-  // ---- epilogue ----
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  if (n_chunks > 1) {
+    // partial sums of a k-chunk: 8 KB per store instruction, contiguous over the workgroup
+    float* part = sk.ws + ((size_t)(slot - sk.full_items) * sk.split + chunk) * 65536 + tid * 4;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          floatx4_t v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+          *reinterpret_cast<floatx4_t*>(part + ((i * 2 + j) * 4 + q) * 2048) = v;
+        }
+    return;
+  }
   __syncthreads();                       // every wave is done with the ring
+  epilogue256<EPI>(g, acc, m0, n0, wave, lane, smem);
+}
+
+// Adds up the k-chunks of the split tiles and sends the sums through the epilogue.
+template <int EPI>
+__global__ __launch_bounds__(512) void gemm256_fixup_kernel(GemmArgs g, int tiles_m, int tiles_n, int per_xcd,
+                                                            int group_m, SplitK sk) {
+  int m0, n0;
+  if (!tile_origin(sk.full_items + blockIdx.x, tiles_m, tiles_n, per_xcd, group_m, m0, n0)) return;
+  extern __shared__ u32x4_t smem[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  floatx16_t acc[4][2];
+  const float* part = sk.ws + (size_t)blockIdx.x * sk.split * 65536 + tid * 4;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        floatx4_t v = *reinterpret_cast<const floatx4_t*>(part + ((i * 2 + j) * 4 + q) * 2048);
+        for (int c = 1; c < sk.split; ++c) {
+          const floatx4_t u = *reinterpret_cast<const floatx4_t*>(part + (size_t)c * 65536 + ((i * 2 + j) * 4 + q) * 2048);
+          v[0] += u[0]; v[1] += u[1]; v[2] += u[2]; v[3] += u[3];
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[i][j][4 * q + e] = v[e];
+      }
+  epilogue256<EPI>(g, acc, m0, n0, wave, lane, smem);
+}
+
+template <int EPI>
+__device__ __forceinline__ void epilogue256(const GemmArgs& g, floatx16_t (&acc)[4][2], int m0, int n0, int wave,
+                                            int lane, u32x4_t* smem) {
+  const int wm0 = (wave & 1) * 128, wn0 = (wave >> 1) * 64;
+  const int lr = lane & 31, lh = lane >> 5;
+  const bool natural = (EPI == EPI_QKV) && (n0 + wn0 >= 2 * g.d);
   char* region = reinterpret_cast<char*>(smem) + wave * STAGE_REGION;
   const int mw = m0 + wm0, nw = n0 + wn0;            // origin of this wave's sub-tile
 
@@ -647,18 +729,48 @@ hipError_t launch_gemm256(const GemmArgs& g, hipStream_t st) {
   int tiles_m = (g.m + 255) / 256, tiles_n = (g.n + 255) / 256;
   int n_tiles = tiles_m * tiles_n;
   int per_xcd = (n_tiles + 7) / 8;
-  dim3 grid(per_xcd * 8), block(512);
+  const int slots = per_xcd * 8;
+  // operand panels of a long-k problem are several MB each: shorter groups of row tiles keep
+  // the set that is live in an XCD's L2 small enough
+  const int group_m = g.k >= 8192 ? 4 : 8;
+  // The chip runs 256 workgroups at a time.  When the last round of tiles fills at most half of
+  // it, those tiles are cut along k so that the round takes 1/split of a tile's time.  Measured
+  // at the 17776-token shapes: worth 9-12 % after 3 full rounds (FFN2, k = 12288: split 3), 2 %
+  // with short k (out-projection: split 2), nothing after 13 rounds, where the workgroups have
+  // drifted apart and the tail is already ragged; chunks under 24 stages cost more than they save.
+  SplitK sk;
+  sk.full_items = slots / 256 * 256;
+  sk.split = 1;
+  sk.ws = g.splitk_ws;
+  const int n_rem = slots - sk.full_items;
+  if (g.splitk_ws != nullptr && n_rem > 0 && sk.full_items <= 8 * 256) {
+    int split = 256 / n_rem;
+    split = std::min(split, (g.k / SBK) / 24);
+    split = std::min(split, 8);
+    split = (int)std::min<size_t>((size_t)split, g.splitk_ws_bytes / ((size_t)n_rem * 262144));
+    sk.split = std::max(split, 1);
+  }
+  if (sk.split == 1) sk.full_items = slots;
+  const int n_split_tiles = slots - sk.full_items;
+  dim3 grid(sk.full_items + n_split_tiles * sk.split), block(512);
 #define HERO_GEMM256_LAUNCH(E)                                                                           \
   do {                                                                                                   \
     auto kern = gemm256_kernel<E>;                                                                       \
+    auto fix = gemm256_fixup_kernel<E>;                                                                  \
     static bool attr_set = false;                                                                        \
     if (!attr_set) {                                                                                     \
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                            \
                                          hipFuncAttributeMaxDynamicSharedMemorySize, GEMM256_LDS);       \
       if (e != hipSuccess) return e;                                                                     \
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(fix),                                        \
+                              hipFuncAttributeMaxDynamicSharedMemorySize, GEMM256_LDS);                  \
+      if (e != hipSuccess) return e;                                                                     \
       attr_set = true;                                                                                   \
     }                                                                                                    \
-    hipLaunchKernelGGL(kern, grid, block, GEMM256_LDS, st, g, tiles_m, tiles_n, per_xcd);                \
+    hipLaunchKernelGGL(kern, grid, block, GEMM256_LDS, st, g, tiles_m, tiles_n, per_xcd, group_m, sk);   \
+    if (n_split_tiles > 0)                                                                               \
+      hipLaunchKernelGGL(fix, dim3(n_split_tiles), block, GEMM256_LDS, st, g, tiles_m, tiles_n, per_xcd, \
+                         group_m, sk);                                                                   \
   } while (0)
   switch (g.epilogue) {
     case EPI_PLAIN: HERO_GEMM256_LAUNCH(EPI_PLAIN); break;
@@ -718,6 +830,5 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t st) {
   // (a wave's columns must lie inside one of the Q / K / V thirds, so the 128-wide wave tiles need d % 128 == 0)
   const bool qkv_split_ok = g.epilogue != EPI_QKV || g.d % 128 == 0;
   if (big_tiles >= 128 && qkv_split_ok) return launch_gemm256(g, st);
-  if (big_tiles >= 128 && qkv_split_ok) return launch_cfg<256, 256, 128, 128>(g, st);
   return launch_cfg<128, 128, 64, 64>(g, st);
 }

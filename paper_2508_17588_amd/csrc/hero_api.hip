@@ -99,7 +99,7 @@ struct Layout {
   size_t t_off[2], t_bytes;      // fp32 sums of the deep layers' features (two generations); 0 bytes if < 2 deep layers
   size_t cache_bytes;
   // workspace
-  size_t idx_off, a_off, q_off, o_off, f_off, ktmp_off, vtmp_off, ws_bytes;
+  size_t idx_off, a_off, q_off, o_off, f_off, ktmp_off, vtmp_off, splitk_off, splitk_bytes, ws_bytes;
 };
 
 Layout make_layout(const hero_config& c) {
@@ -131,6 +131,10 @@ Layout make_layout(const hero_config& c) {
     L.vtmp_off = w;
     w += L.vt_bytes;
   }
+  // partial sums of GEMM tiles cut along k: at most 256 blocks of 256 x 256 fp32 (large problems only)
+  L.splitk_off = w;
+  L.splitk_bytes = L.n_tokens >= 2048 ? (size_t)256 * 262144 : 0;
+  w += L.splitk_bytes;
   L.ws_bytes = w;
   return L;
 }
@@ -176,6 +180,7 @@ struct hero_cache {
   int32_t* ages = nullptr;
   int32_t* idx = nullptr;
   bf16_t *a = nullptr, *q = nullptr, *o = nullptr, *f = nullptr, *ktmp = nullptr, *vtmp = nullptr;
+  float* splitk = nullptr;        // GEMM k-split partial sums (nullptr when the problem is too small to need them)
   std::vector<LayerState> layers;
   // deep-stack sums: slot i holds sum_l S_cur^l taken when the deep layers' fill counts were
   // t_key[i] (t_is_prev[i] false), or the matching previous-generation sum (t_is_prev[i] true)
@@ -239,6 +244,7 @@ int run_block_rows(hero_cache_t c, LayerState& ls, void* x, const int32_t* rows,
   g.c = c->q; g.k_out = k_dst; g.vt_out = vt_dst; g.ld_vt = c->lay.n_pad; g.d = d;
   // softmax scale and the change to base 2 are folded into Q before its single bf16 rounding
   g.q_scale = 1.4426950408889634f / sqrtf((float)cfg.head_dim);
+  g.splitk_ws = c->splitk; g.splitk_ws_bytes = c->lay.splitk_bytes;
   PROF_LAUNCH(c, HERO_PROF_GEMM_QKV, 6.0 * rd * d, st, launch_gemm(g, st));
 
   AttnArgs at;
@@ -250,6 +256,7 @@ int run_block_rows(hero_cache_t c, LayerState& ls, void* x, const int32_t* rows,
   memset(&g, 0, sizeof(g));
   g.a = c->o; g.w = (const bf16_t*)w.w_o; g.bias = (const bf16_t*)w.b_o;
   g.m = n_rows; g.n = d; g.k = d; g.epilogue = EPI_SCATTER; g.rows = rows; g.c = s_dst;
+  g.splitk_ws = c->splitk; g.splitk_ws_bytes = c->lay.splitk_bytes;
   PROF_LAUNCH(c, HERO_PROF_GEMM_O, 2.0 * rd * d, st, launch_gemm(g, st));
 
   PROF_LAUNCH(c, HERO_PROF_LN, rd * (xsz + 4.0), st,
@@ -258,11 +265,13 @@ int run_block_rows(hero_cache_t c, LayerState& ls, void* x, const int32_t* rows,
   memset(&g, 0, sizeof(g));
   g.a = c->a; g.w = (const bf16_t*)w.w_ff1; g.bias = (const bf16_t*)w.b_ff1;
   g.m = n_rows; g.n = cfg.ffn_dim; g.k = d; g.epilogue = EPI_GELU; g.c = c->f;
+  g.splitk_ws = c->splitk; g.splitk_ws_bytes = c->lay.splitk_bytes;
   PROF_LAUNCH(c, HERO_PROF_GEMM_FF1, 2.0 * rd * cfg.ffn_dim, st, launch_gemm(g, st));
 
   memset(&g, 0, sizeof(g));
   g.a = c->f; g.w = (const bf16_t*)w.w_ff2; g.bias = (const bf16_t*)w.b_ff2;
   g.m = n_rows; g.n = d; g.k = cfg.ffn_dim; g.epilogue = EPI_SCATTER_ADD; g.rows = rows; g.c = s_dst;
+  g.splitk_ws = c->splitk; g.splitk_ws_bytes = c->lay.splitk_bytes;
   PROF_LAUNCH(c, HERO_PROF_GEMM_FF2, 2.0 * rd * cfg.ffn_dim, st, launch_gemm(g, st));
   return HERO_OK;
 }
@@ -380,6 +389,7 @@ int hero_cache_create(const hero_config* cfg, void* dev_cache, size_t cache_byte
   c->f = (bf16_t*)(c->ws + L.f_off);
   c->ktmp = (bf16_t*)(c->ws + L.ktmp_off);
   c->vtmp = (bf16_t*)(c->ws + L.vtmp_off);
+  c->splitk = L.splitk_bytes ? (float*)(c->ws + L.splitk_off) : nullptr;
   c->layers.resize(cfg->n_layers);
   if (L.t_bytes) { c->t[0] = (float*)(c->cache + L.t_off[0]); c->t[1] = (float*)(c->cache + L.t_off[1]); }
   size_t off = align_up((size_t)L.n_video * 4, 256);
@@ -630,18 +640,25 @@ int hero_gather_ln(const void* dev_x, int32_t x_dtype, const void* dev_add_bf16,
   return HERO_OK;
 }
 
-int hero_linear(const void* dev_a, const void* dev_w, const void* dev_bias, void* dev_c, int32_t m, int32_t n,
-                int32_t k, int32_t act, void* stream) {
+int hero_linear_scratch(const void* dev_a, const void* dev_w, const void* dev_bias, void* dev_c, int32_t m,
+                        int32_t n, int32_t k, int32_t act, void* dev_scratch, size_t scratch_bytes, void* stream) {
   if (!dev_a || !dev_w || !dev_bias || !dev_c) return fail(HERO_ERR_INVALID_ARG, "null pointer");
   if (m < 0 || n <= 0 || k <= 0) return fail(HERO_ERR_INVALID_ARG, "bad sizes");
   if (k % 64 != 0 || n % 64 != 0) return fail(HERO_ERR_SHAPE, "k and n must be multiples of 64");
   if (act != 0 && act != 1) return fail(HERO_ERR_INVALID_ARG, "act must be 0 or 1");
+  if (dev_scratch != nullptr && (uintptr_t)dev_scratch % 16 != 0) return fail(HERO_ERR_INVALID_ARG, "scratch must be 16-byte aligned");
   GemmArgs g;
   memset(&g, 0, sizeof(g));
   g.a = (const bf16_t*)dev_a; g.w = (const bf16_t*)dev_w; g.bias = (const bf16_t*)dev_bias;
   g.m = m; g.n = n; g.k = k; g.epilogue = act ? EPI_GELU : EPI_PLAIN; g.c = (bf16_t*)dev_c;
+  g.splitk_ws = (float*)dev_scratch; g.splitk_ws_bytes = dev_scratch ? scratch_bytes : 0;
   HIP_TRY(launch_gemm(g, (hipStream_t)stream));
   return HERO_OK;
+}
+
+int hero_linear(const void* dev_a, const void* dev_w, const void* dev_bias, void* dev_c, int32_t m, int32_t n,
+                int32_t k, int32_t act, void* stream) {
+  return hero_linear_scratch(dev_a, dev_w, dev_bias, dev_c, m, n, k, act, nullptr, 0, stream);
 }
 
 int hero_attention(const void* dev_q, const void* dev_k, const void* dev_vt, int64_t ld_vt, void* dev_o,

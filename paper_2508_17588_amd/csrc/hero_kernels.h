@@ -58,6 +58,8 @@ struct GemmArgs {
   int64_t ld_vt;
   int32_t d;            // QKV: hidden
   float q_scale;        // QKV: the Q third is stored multiplied by this (softmax scale folded into Q)
+  float* splitk_ws;     // optional device scratch for k-split partial sums (nullptr: never split)
+  size_t splitk_ws_bytes;
 };
 
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t st);

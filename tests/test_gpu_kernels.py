@@ -104,6 +104,30 @@ def test_linear(m, n, k, act):
     assert float((c[m:] - 7.0).abs().max()) == 0.0              # rows past M untouched
 
 
+@pytest.mark.parametrize("m,n,k,act,scratch_mib", [
+    (2040, 4096, 3072, 0, 64),       # 128 tiles, all cut in two
+    (2700, 6144, 4608, 1, 64),       # 264 tiles: 256 whole, 8 cut in three
+    (2700, 6144, 4608, 0, 5),        # scratch for two chunks per tile only
+    (2700, 6144, 4608, 0, 1),        # scratch too small to cut anything
+    (2700, 6144, 1024, 0, 64),       # k too short to cut
+    (4000, 3072, 3072, 0, 64),       # 192 tiles: the round is too full to cut
+])
+def test_linear_with_k_split(m, n, k, act, scratch_mib):
+    say(f"linear (k-split) m={m} n={n} k={k} act={act} scratch={scratch_mib} MiB")
+    a = rnd(13, m, k)
+    w = rnd(14, n, k, scale=1.0 / np.sqrt(k))
+    b = rnd(15, n, scale=0.5)
+    c = torch.full((m + 2, n), 7.0, dtype=torch.bfloat16, device="cuda")
+    scratch = torch.full((scratch_mib << 18,), float("nan"), dtype=torch.float32, device="cuda")
+    B.hero_linear_scratch(to_dev_bf16(a), to_dev_bf16(w), to_dev_bf16(b), c, scratch, act)
+    torch.cuda.synchronize()
+    want = O.linear(a.astype(np.float64), w.astype(np.float64), b.astype(np.float64))
+    if act:
+        want = O.gelu_tanh(want)
+    assert_close(to_host_f64(c[:m]), want, "linear with k-split")
+    assert float((c[m:] - 7.0).abs().max()) == 0.0
+
+
 # ---------------------------------------------------------------- attention
 
 def vt_padded(v, ld):

@@ -110,6 +110,7 @@ def test_null_and_small_buffers_are_rejected_before_any_gpu_work(lib):
     assert lib.hero_linear(None, None, None, None, 1, 64, 64, 0, None) == B.HERO_ERR_INVALID_ARG
     p = ctypes.c_void_p(256)
     assert lib.hero_linear(p, p, p, p, 1, 60, 64, 0, None) == B.HERO_ERR_SHAPE
+    assert lib.hero_linear_scratch(p, p, p, p, 1, 64, 64, 0, ctypes.c_void_p(260), 1 << 20, None) == B.HERO_ERR_INVALID_ARG
     assert lib.hero_attention(p, p, p, 100, p, 1, 100, 1, 64, None) == B.HERO_ERR_SHAPE
     assert lib.hero_attention(p, p, p, 128, p, 1, 100, 1, 48, None) == B.HERO_ERR_SHAPE
     assert lib.hero_axpy_features(p, 1, p, None, 0.0, 12, None) == B.HERO_ERR_SHAPE
