@@ -124,8 +124,34 @@ def main():
     torch.cuda.synchronize()
 
     K = args.steps
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(K + 1)]
+
+    def kernel_table(prof):
+        table = {}
+        for name, (ms, cnt, work) in prof.items():
+            kind = name.split("/")[0]
+            mfma = kind.startswith("gemm") or kind == "attention"
+            rate = work / (ms * 1e-3) / (1e12 if mfma else 1e9) if ms > 0 else 0.0
+            table[name] = {"total_ms": round(ms, 3), "launches": cnt, "avg_ms": round(ms / cnt, 4),
+                           "achieved": round(rate, 2), "unit": "TFLOP/s" if mfma else "GB/s",
+                           "frac": round(rate / (PEAK_BF16_TFLOPS if mfma else PEAK_HBM_GBS), 4)}
+        return table
+
+    # Pass 1 (not timed): the same K steps with every kernel launch bracketed by HIP events, for
+    # the per-kernel table and to find the dominant kernel.  Each bracket costs two stream
+    # markers (about 1 % of the step in total), so the timed pass brackets the dominant kind only.
     cache.hero_profile_begin()
+    for s in range(K):
+        x.copy_(x0)
+        cache.hero_step(x, s)
+    torch.cuda.synchronize()
+    kernels = kernel_table(cache.hero_profile_end())
+    dominant = max(kernels, key=lambda k: kernels[k]["total_ms"])
+    cache.hero_cache_reset()
+    torch.cuda.synchronize()
+
+    # Pass 2 (timed): K steps, HIP events around the dominant kind's launches and around each step.
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(K + 1)]
+    cache.hero_profile_begin_kinds([dominant.split("/")[0]])
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     ev[0].record()
@@ -135,7 +161,7 @@ def main():
         ev[s + 1].record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    prof = cache.hero_profile_end()
+    kernels.update(kernel_table(cache.hero_profile_end()))      # the dominant kind: as measured in the timed region
     assert bool(torch.isfinite(x).all()), "non-finite activations"
 
     ms_per_step = (t1 - t0) * 1e3 / K
@@ -144,14 +170,6 @@ def main():
     cached_ms = [t for s, t in enumerate(step_ms) if s % cfg.interval != 0]
     mean = lambda v: sum(v) / len(v) if v else None
 
-    kernels = {}
-    for name, (ms, cnt, work) in prof.items():
-        kind = name.split("/")[0]
-        mfma = kind.startswith("gemm") or kind == "attention"
-        rate = work / (ms * 1e-3) / (1e12 if mfma else 1e9) if ms > 0 else 0.0
-        kernels[name] = {"total_ms": round(ms, 3), "launches": cnt, "avg_ms": round(ms / cnt, 4),
-                         "achieved": round(rate, 2), "unit": "TFLOP/s" if mfma else "GB/s",
-                         "frac": round(rate / (PEAK_BF16_TFLOPS if mfma else PEAK_HBM_GBS), 4)}
     dominant = max(kernels, key=lambda k: kernels[k]["total_ms"])
     dk = kernels[dominant]
     mfma = dk["unit"] == "TFLOP/s"
@@ -177,6 +195,8 @@ def main():
         "speedup_vs_all_full": round(mean(full_ms) / ms_per_step, 3) if full_ms else None,
         "roofline": roofline,
         "kernels": kernels,
+        "kernels_note": "entries of the dominant kind: HIP events inside the timed region; all others: an untimed "
+                        "pass over the same steps with every launch bracketed",
         "paper_context": "paper reports 1.73x (FLOPs ratio; 1.68x by latency) on A100-80G, Aether, M=2, K=20, R=0.2",
     }
     if not args.no_cpu_baseline:

@@ -157,6 +157,8 @@ int hero_cache_state(hero_cache_t c, int32_t* n_full, int32_t* last_full_step);
  * Slot = kind for launches made by hero_full_layer, kind + HERO_PROF_KINDS otherwise.
  * HERO_PROF_EXTRAP covers both the per-layer update and hero_step's one-pass update of the
  * whole deep stack; HERO_PROF_DEEPSUM is the once-per-generation summation behind the latter.
+ * A full layer of a large problem adds its features to x inside the FFN2 kernel: it then has
+ * no HERO_PROF_RESID launch and the time is part of HERO_PROF_GEMM_FF2.
  * The three output arrays have 2 * HERO_PROF_KINDS entries (any may be NULL). */
 enum {
   HERO_PROF_SELECT = 0, HERO_PROF_LN = 1, HERO_PROF_GEMM_QKV = 2, HERO_PROF_ATTN = 3,
@@ -164,6 +166,9 @@ enum {
   HERO_PROF_EXTRAP = 8, HERO_PROF_DEEPSUM = 9, HERO_PROF_KINDS = 10
 };
 int hero_profile_begin(hero_cache_t c);
+/* The same, bracketing only the kinds whose bit (1u << kind) is set in kind_mask: each bracket
+ * costs two stream markers, which a timed run may want to spend on a few kinds only. */
+int hero_profile_begin_kinds(hero_cache_t c, uint32_t kind_mask);
 int hero_profile_end(hero_cache_t c, void* stream, double* ms, int64_t* launches, double* work);
 
 /* ---- building blocks, exposed so each kernel can be checked on its own ------------- */

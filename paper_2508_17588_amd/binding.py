@@ -36,7 +36,7 @@ EXPORTS = (
     "hero_last_error", "hero_num_selected", "hero_cache_bytes", "hero_cache_create",
     "hero_cache_destroy", "hero_cache_reset", "hero_set_layer_weights", "hero_full_layer",
     "hero_select", "hero_reset_ages", "hero_refresh_layer", "hero_extrapolate_layer", "hero_step",
-    "hero_cache_view", "hero_cache_state", "hero_profile_begin", "hero_profile_end", "hero_gather_ln", "hero_linear", "hero_linear_scratch",
+    "hero_cache_view", "hero_cache_state", "hero_profile_begin", "hero_profile_begin_kinds", "hero_profile_end", "hero_gather_ln", "hero_linear", "hero_linear_scratch",
     "hero_attention",
     "hero_axpy_features",
 )
@@ -91,6 +91,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
         "hero_cache_view": [P, I, I, POINTER(c_void_p), POINTER(c_int64)],
         "hero_cache_state": [P, POINTER(c_int32), POINTER(c_int32)],
         "hero_profile_begin": [P],
+        "hero_profile_begin_kinds": [P, ctypes.c_uint32],
         "hero_profile_end": [P, P, POINTER(ctypes.c_double), POINTER(c_int64), POINTER(ctypes.c_double)],
         "hero_gather_ln": [P, I, P, P, I, I, P, P, c_float, P, P],
         "hero_linear": [P, P, P, P, I, I, I, I, P],
@@ -238,6 +239,13 @@ class HeroCache:
 
     def hero_profile_begin(self):
         _check(self.lib.hero_profile_begin(self.handle))
+
+    def hero_profile_begin_kinds(self, kinds):
+        """Bracket only the named kinds (entries of PROF_KINDS)."""
+        mask = 0
+        for k in kinds:
+            mask |= 1 << PROF_KINDS.index(k)
+        _check(self.lib.hero_profile_begin_kinds(self.handle, mask))
 
     def hero_profile_end(self):
         """-> {slot_name: (ms, launches, work)}; slot names end in '/full' or '/cached'."""

@@ -380,7 +380,7 @@ __device__ __forceinline__ bool tile_origin(int slot, int tiles_m, int tiles_n, 
 
 template <int EPI>
 __device__ __forceinline__ void epilogue256(const GemmArgs& g, floatx16_t (&acc)[4][2], int m0, int n0, int wave,
-                                            int lane, u32x4_t* smem);
+                                            int lane, char* region);
 
 template <int EPI>
 __global__ __launch_bounds__(512) void gemm256_kernel(GemmArgs g, int tiles_m, int tiles_n, int per_xcd,
@@ -530,45 +530,47 @@ __global__ __launch_bounds__(512) void gemm256_kernel(GemmArgs g, int tiles_m, i
     return;
   }
   __syncthreads();                       // every wave is done with the ring
-  epilogue256<EPI>(g, acc, m0, n0, wave, lane, smem);
+  epilogue256<EPI>(g, acc, m0, n0, wave, lane, reinterpret_cast<char*>(smem) + wave * STAGE_REGION);
 }
 
-// Adds up the k-chunks of the split tiles and sends the sums through the epilogue.
+// Adds up the k-chunks of the split tiles and sends the sums through the epilogue.  One
+// single-wave workgroup per 128 x 64 wave sub-tile (8 per tile), so that even a few dozen split
+// tiles spread over the whole chip; the 32 loads of a chunk are independent and in flight together.
 template <int EPI>
-__global__ __launch_bounds__(512) void gemm256_fixup_kernel(GemmArgs g, int tiles_m, int tiles_n, int per_xcd,
-                                                            int group_m, SplitK sk) {
+__global__ __launch_bounds__(64) void gemm256_fixup_kernel(GemmArgs g, int tiles_m, int tiles_n, int per_xcd,
+                                                           int group_m, SplitK sk) {
+  const int tile = blockIdx.x >> 3, wave = blockIdx.x & 7;
   int m0, n0;
-  if (!tile_origin(sk.full_items + blockIdx.x, tiles_m, tiles_n, per_xcd, group_m, m0, n0)) return;
+  if (!tile_origin(sk.full_items + tile, tiles_m, tiles_n, per_xcd, group_m, m0, n0)) return;
   extern __shared__ u32x4_t smem[];
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lane = threadIdx.x;
   floatx16_t acc[4][2];
-  const float* part = sk.ws + (size_t)blockIdx.x * sk.split * 65536 + tid * 4;
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        floatx4_t v = *reinterpret_cast<const floatx4_t*>(part + ((i * 2 + j) * 4 + q) * 2048);
-        for (int c = 1; c < sk.split; ++c) {
-          const floatx4_t u = *reinterpret_cast<const floatx4_t*>(part + (size_t)c * 65536 + ((i * 2 + j) * 4 + q) * 2048);
-          v[0] += u[0]; v[1] += u[1]; v[2] += u[2]; v[3] += u[3];
-        }
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+  const float* part = sk.ws + (size_t)tile * sk.split * 65536 + (wave * 64 + lane) * 4;
+  for (int c = 0; c < sk.split; ++c, part += 65536) {
+    floatx4_t v[32];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) acc[i][j][4 * q + e] = v[e];
-      }
-  epilogue256<EPI>(g, acc, m0, n0, wave, lane, smem);
+    for (int x = 0; x < 32; ++x) v[x] = __builtin_nontemporal_load(reinterpret_cast<const floatx4_t*>(part + x * 2048));
+#pragma unroll
+    for (int x = 0; x < 32; ++x)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc[x >> 3][(x >> 2) & 1][4 * (x & 3) + e] += v[x][e];
+  }
+  epilogue256<EPI>(g, acc, m0, n0, wave, lane, reinterpret_cast<char*>(smem));
 }
 
 template <int EPI>
 __device__ __forceinline__ void epilogue256(const GemmArgs& g, floatx16_t (&acc)[4][2], int m0, int n0, int wave,
-                                            int lane, u32x4_t* smem) {
+                                            int lane, char* region) {
   const int wm0 = (wave & 1) * 128, wn0 = (wave >> 1) * 64;
   const int lr = lane & 31, lh = lane >> 5;
   const bool natural = (EPI == EPI_QKV) && (n0 + wn0 >= 2 * g.d);
-  char* region = reinterpret_cast<char*>(smem) + wave * STAGE_REGION;
-  const int mw = m0 + wm0, nw = n0 + wn0;            // origin of this wave's sub-tile
+  const int mw = m0 + wm0, nw = n0 + wn0;            // origin of this wave's sub-tile; region: its LDS staging space
 
   if (EPI == EPI_QKV && natural) {
     // acc[i][j][4q+e] = C[m = mw + 32i + 8q + 4lh + e][n = nw + 32j + lr]; stage [n][m]
@@ -688,6 +690,23 @@ __device__ __forceinline__ void epilogue256(const GemmArgs& g, floatx16_t (&acc)
           for (int e = 0; e < 4; ++e)
             out[e] = pack_bf16x2_hw(v[2 * e] + unpack_lo(old[e]), v[2 * e + 1] + unpack_hi(old[e]));
           *d = out;
+          if (g.x != nullptr) {
+            // residual add with the feature as stored (rounded), so x matches x += S done afterwards
+            if (g.x_fp32) {
+              floatx4_t* xp = reinterpret_cast<floatx4_t*>(static_cast<float*>(g.x) + row * ld + n);
+              floatx4_t x0 = xp[0], x1 = xp[1];
+              x0[0] += unpack_lo(out[0]); x0[1] += unpack_hi(out[0]); x0[2] += unpack_lo(out[1]); x0[3] += unpack_hi(out[1]);
+              x1[0] += unpack_lo(out[2]); x1[1] += unpack_hi(out[2]); x1[2] += unpack_lo(out[3]); x1[3] += unpack_hi(out[3]);
+              xp[0] = x0; xp[1] = x1;
+            } else {
+              u32x4_t* xp = reinterpret_cast<u32x4_t*>(static_cast<bf16_t*>(g.x) + row * ld + n);
+              u32x4_t xv = *xp, xo;
+#pragma unroll
+              for (int e = 0; e < 4; ++e)
+                xo[e] = pack_bf16x2(unpack_lo(xv[e]) + unpack_lo(out[e]), unpack_hi(xv[e]) + unpack_hi(out[e]));
+              *xp = xo;
+            }
+          }
         }
       }
     }
@@ -735,9 +754,10 @@ hipError_t launch_gemm256(const GemmArgs& g, hipStream_t st) {
   const int group_m = g.k >= 8192 ? 4 : 8;
   // The chip runs 256 workgroups at a time.  When the last round of tiles fills at most half of
   // it, those tiles are cut along k so that the round takes 1/split of a tile's time.  Measured
-  // at the 17776-token shapes: worth 9-12 % after 3 full rounds (FFN2, k = 12288: split 3), 2 %
-  // with short k (out-projection: split 2), nothing after 13 rounds, where the workgroups have
-  // drifted apart and the tail is already ragged; chunks under 24 stages cost more than they save.
+  // at the 17776-token shapes: 9 % faster after 3 full rounds of long tiles (FFN2, k = 12288,
+  // split 3); no gain when the chunks get shorter than about 32 stages (k = 3072 problems: the
+  // fix-up pass costs what the shorter round saves) or after 13 rounds, where the workgroups
+  // have drifted apart and the tail is ragged anyway.
   SplitK sk;
   sk.full_items = slots / 256 * 256;
   sk.split = 1;
@@ -745,7 +765,7 @@ hipError_t launch_gemm256(const GemmArgs& g, hipStream_t st) {
   const int n_rem = slots - sk.full_items;
   if (g.splitk_ws != nullptr && n_rem > 0 && sk.full_items <= 8 * 256) {
     int split = 256 / n_rem;
-    split = std::min(split, (g.k / SBK) / 24);
+    split = std::min(split, (g.k / SBK) / 32);
     split = std::min(split, 8);
     split = (int)std::min<size_t>((size_t)split, g.splitk_ws_bytes / ((size_t)n_rem * 262144));
     sk.split = std::max(split, 1);
@@ -762,15 +782,12 @@ hipError_t launch_gemm256(const GemmArgs& g, hipStream_t st) {
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                            \
                                          hipFuncAttributeMaxDynamicSharedMemorySize, GEMM256_LDS);       \
       if (e != hipSuccess) return e;                                                                     \
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(fix),                                        \
-                              hipFuncAttributeMaxDynamicSharedMemorySize, GEMM256_LDS);                  \
-      if (e != hipSuccess) return e;                                                                     \
       attr_set = true;                                                                                   \
     }                                                                                                    \
     hipLaunchKernelGGL(kern, grid, block, GEMM256_LDS, st, g, tiles_m, tiles_n, per_xcd, group_m, sk);   \
     if (n_split_tiles > 0)                                                                               \
-      hipLaunchKernelGGL(fix, dim3(n_split_tiles), block, GEMM256_LDS, st, g, tiles_m, tiles_n, per_xcd, \
-                         group_m, sk);                                                                   \
+      hipLaunchKernelGGL(fix, dim3(n_split_tiles * 8), dim3(64), STAGE_REGION, st, g, tiles_m, tiles_n,  \
+                         per_xcd, group_m, sk);                                                          \
   } while (0)
   switch (g.epilogue) {
     case EPI_PLAIN: HERO_GEMM256_LAUNCH(EPI_PLAIN); break;
@@ -818,6 +835,18 @@ hipError_t launch_cfg(const GemmArgs& g, hipStream_t st) {
 
 }  // namespace
 
+namespace {
+bool uses_large_tiles(const GemmArgs& g) {
+  // large problems: 256x256 tiles, 8 waves of 128x64; small ones: 128x128 tiles, 4 waves of 64x64
+  const int64_t big_tiles = (int64_t)((g.m + 255) / 256) * ((g.n + 255) / 256);
+  // (a wave's columns must lie inside one of the Q / K / V thirds)
+  const bool qkv_split_ok = g.epilogue != EPI_QKV || g.d % 128 == 0;
+  return big_tiles >= 128 && qkv_split_ok;
+}
+}  // namespace
+
+bool gemm_can_update_x(const GemmArgs& g) { return g.epilogue == EPI_SCATTER_ADD && uses_large_tiles(g); }
+
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t st) {
   if (g.m <= 0 || g.n <= 0) return hipSuccess;
   if (g.k <= 0 || g.k % BK != 0 || g.n % 64 != 0) return hipErrorInvalidValue;
@@ -825,10 +854,7 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t st) {
   // operands are addressed with 32-bit byte offsets
   if (((int64_t)g.m + 512) * g.k * 2 >= (int64_t)1 << 32 || ((int64_t)g.n + 512) * g.k * 2 >= (int64_t)1 << 32)
     return hipErrorInvalidValue;
-  // large problems: 256x256 tiles, 8 waves of 128x64; small ones: 128x128 tiles, 4 waves of 64x64
-  int64_t big_tiles = (int64_t)((g.m + 255) / 256) * ((g.n + 255) / 256);
-  // (a wave's columns must lie inside one of the Q / K / V thirds, so the 128-wide wave tiles need d % 128 == 0)
-  const bool qkv_split_ok = g.epilogue != EPI_QKV || g.d % 128 == 0;
-  if (big_tiles >= 128 && qkv_split_ok) return launch_gemm256(g, st);
+  if (uses_large_tiles(g)) return launch_gemm256(g, st);
+  if (g.x != nullptr) return hipErrorInvalidValue;       // only the large-tile epilogue updates x
   return launch_cfg<128, 128, 64, 64>(g, st);
 }

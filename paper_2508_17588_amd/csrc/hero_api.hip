@@ -142,6 +142,7 @@ Layout make_layout(const hero_config& c) {
 struct Profiler {
   struct Rec { int slot; size_t e0, e1; double work; };
   bool on = false;
+  uint32_t mask = 0xffffffffu;       // kinds that are bracketed while on
   std::vector<hipEvent_t> pool;
   size_t used = 0;
   std::vector<Rec> recs;
@@ -210,7 +211,7 @@ int check_layer(hero_cache_t c, int layer) {
 // Launch `expr` on stream `st`; when profiling is on, bracket it with events.
 #define PROF_LAUNCH(c, kind, work_, st, expr)                                        \
   do {                                                                               \
-    if ((c)->prof.on) {                                                              \
+    if ((c)->prof.on && (((c)->prof.mask >> (kind)) & 1u)) {                         \
       hipEvent_t e0_, e1_; size_t i0_, i1_;                                          \
       HIP_TRY((c)->prof.next(&e0_, &i0_));                                           \
       HIP_TRY((c)->prof.next(&e1_, &i1_));                                           \
@@ -224,9 +225,11 @@ int check_layer(hero_cache_t c, int layer) {
   } while (0)
 
 // The block of Eq. 2 on the rows listed in `rows` (nullptr = all N rows), writing K/V to
-// (k_dst, vt_dst) and the branch features to s_dst; ends before the residual add.
+// (k_dst, vt_dst) and the branch features to s_dst.  It ends before the residual add, unless
+// fuse_resid is given and the FFN2 kernel can add the stored features of its rows to x itself
+// (then *fuse_resid is set; only valid when the listed rows are all the rows x += S applies to).
 int run_block_rows(hero_cache_t c, LayerState& ls, void* x, const int32_t* rows, int n_rows, bf16_t* k_dst,
-                   bf16_t* vt_dst, bf16_t* s_dst, hipStream_t st) {
+                   bf16_t* vt_dst, bf16_t* s_dst, hipStream_t st, bool* fuse_resid = nullptr) {
   const hero_config& cfg = c->cfg;
   const bool x_fp32 = cfg.resid_dtype == HERO_DTYPE_FP32;
   const int d = cfg.hidden;
@@ -271,6 +274,10 @@ int run_block_rows(hero_cache_t c, LayerState& ls, void* x, const int32_t* rows,
   memset(&g, 0, sizeof(g));
   g.a = c->f; g.w = (const bf16_t*)w.w_ff2; g.bias = (const bf16_t*)w.b_ff2;
   g.m = n_rows; g.n = d; g.k = cfg.ffn_dim; g.epilogue = EPI_SCATTER_ADD; g.rows = rows; g.c = s_dst;
+  if (fuse_resid != nullptr) {
+    *fuse_resid = gemm_can_update_x(g);
+    if (*fuse_resid) { g.x = x; g.x_fp32 = x_fp32 ? 1 : 0; }
+  }
   g.splitk_ws = c->splitk; g.splitk_ws_bytes = c->lay.splitk_bytes;
   PROF_LAUNCH(c, HERO_PROF_GEMM_FF2, 2.0 * rd * cfg.ffn_dim, st, launch_gemm(g, st));
   return HERO_OK;
@@ -466,11 +473,13 @@ int hero_full_layer(hero_cache_t c, int32_t layer, void* dev_x, void* stream) {
   bf16_t* k_dst = shallow ? ls.k : c->ktmp;
   bf16_t* vt_dst = shallow ? ls.vt : c->vtmp;
   c->in_full = true;
-  rc = run_block_rows(c, ls, dev_x, nullptr, (int)c->lay.n_tokens, k_dst, vt_dst, ls.s_cur, st);
+  bool resid_done = false;
+  rc = run_block_rows(c, ls, dev_x, nullptr, (int)c->lay.n_tokens, k_dst, vt_dst, ls.s_cur, st, &resid_done);
   if (rc) { c->in_full = false; return rc; }
   const bool x_fp32 = c->cfg.resid_dtype == HERO_DTYPE_FP32;
   const double nd = (double)c->lay.n_tokens * c->cfg.hidden;
   rc = [&]() -> int {
+    if (resid_done) return HERO_OK;
     PROF_LAUNCH(c, HERO_PROF_RESID, nd * (x_fp32 ? 10.0 : 6.0), st,
                 launch_axpy_features(dev_x, x_fp32, ls.s_cur, nullptr, 0.f, c->lay.n_tokens * c->cfg.hidden, st));
     return HERO_OK;
@@ -596,9 +605,12 @@ int hero_cache_state(hero_cache_t c, int32_t* n_full, int32_t* last_full_step) {
   return HERO_OK;
 }
 
-int hero_profile_begin(hero_cache_t c) {
+int hero_profile_begin(hero_cache_t c) { return hero_profile_begin_kinds(c, 0xffffffffu); }
+
+int hero_profile_begin_kinds(hero_cache_t c, uint32_t kind_mask) {
   if (check_handle(c)) return HERO_ERR_INVALID_ARG;
   c->prof.on = true;
+  c->prof.mask = kind_mask;
   c->prof.used = 0;
   c->prof.recs.clear();
   return HERO_OK;

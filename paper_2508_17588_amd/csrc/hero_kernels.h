@@ -60,9 +60,13 @@ struct GemmArgs {
   float q_scale;        // QKV: the Q third is stored multiplied by this (softmax scale folded into Q)
   float* splitk_ws;     // optional device scratch for k-split partial sums (nullptr: never split)
   size_t splitk_ws_bytes;
+  void* x;              // SCATTER_ADD, optional: x[row(m), :] += the stored (rounded) S[row(m), :]  (Alg. 1 residual add)
+  int32_t x_fp32;       // x holds fp32 (else bf16)
 };
 
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t st);
+// whether launch_gemm would honour g.x for this problem (only the large-tile kernel does)
+bool gemm_can_update_x(const GemmArgs& g);
 
 struct AttnArgs {
   const bf16_t* q;      // [r, n_heads*head_dim]
