@@ -164,6 +164,17 @@ def main():
     kernels.update(kernel_table(cache.hero_profile_end()))      # the dominant kind: as measured in the timed region
     assert bool(torch.isfinite(x).all()), "non-finite activations"
 
+    # The per-layer extrapolation kernel (Eq. 5 on one deep layer) is not on hero_step's path any
+    # more (the deep stack is applied in one pass); time it on its own, after the timed region, on
+    # the first deep layer's two generations.
+    if cfg.n_shallow < cfg.n_layers and K > cfg.interval:
+        cache.hero_profile_begin_kinds(["extrap"])
+        for _ in range(20):
+            cache.hero_extrapolate_layer(cfg.n_shallow, x, 1)
+        torch.cuda.synchronize()
+        for name, rec in kernel_table(cache.hero_profile_end()).items():
+            kernels["extrap_layer/standalone"] = rec
+
     ms_per_step = (t1 - t0) * 1e3 / K
     step_ms = [ev[i].elapsed_time(ev[i + 1]) for i in range(K)]
     full_ms = [t for s, t in enumerate(step_ms) if s % cfg.interval == 0]

@@ -752,23 +752,29 @@ hipError_t launch_gemm256(const GemmArgs& g, hipStream_t st) {
   // operand panels of a long-k problem are several MB each: shorter groups of row tiles keep
   // the set that is live in an XCD's L2 small enough
   const int group_m = g.k >= 8192 ? 4 : 8;
-  // The chip runs 256 workgroups at a time.  When the last round of tiles fills at most half of
-  // it, those tiles are cut along k so that the round takes 1/split of a tile's time.  Measured
-  // at the 17776-token shapes: 9 % faster after 3 full rounds of long tiles (FFN2, k = 12288,
-  // split 3); no gain when the chunks get shorter than about 32 stages (k = 3072 problems: the
-  // fix-up pass costs what the shorter round saves) or after 13 rounds, where the workgroups
-  // have drifted apart and the tail is ragged anyway.
+  // The chip runs 256 workgroups at a time, so the last round of tiles may leave most of it
+  // idle.  Cutting those n_rem tiles into s k-chunks makes the round take ceil(n_rem*s/256)/s of
+  // a tile's time, and costs a fix-up pass that moves n_rem*s blocks of 256 KB twice (about
+  // 0.1*n_rem/stages of a tile's time per chunk, measured).  Take the s that minimises the sum,
+  // with chunks of at least 32 stages (shorter ones cost more than they save: k = 3072
+  // problems gain nothing) and only after at most 8 full rounds (later the workgroups have
+  // drifted apart and the tail is ragged anyway).  At the 17776-token shapes this cuts FFN2
+  // (k = 12288; 3 rounds + 72 tiles) in 3 and makes it 9 % faster.
   SplitK sk;
   sk.full_items = slots / 256 * 256;
   sk.split = 1;
   sk.ws = g.splitk_ws;
   const int n_rem = slots - sk.full_items;
   if (g.splitk_ws != nullptr && n_rem > 0 && sk.full_items <= 8 * 256) {
-    int split = 256 / n_rem;
-    split = std::min(split, (g.k / SBK) / 32);
-    split = std::min(split, 8);
-    split = (int)std::min<size_t>((size_t)split, g.splitk_ws_bytes / ((size_t)n_rem * 262144));
-    sk.split = std::max(split, 1);
+    const int stages = g.k / SBK;
+    const int s_max = (int)std::min<size_t>((size_t)std::min(stages / 32, 8),
+                                            g.splitk_ws_bytes / ((size_t)n_rem * 262144));
+    const double per_chunk = 0.1 * n_rem / stages;
+    double best = 1.0;
+    for (int sp = 2; sp <= s_max; ++sp) {
+      const double t = (double)((n_rem * sp + 255) / 256) / sp + per_chunk * sp;
+      if (t < best - 0.02) { best = t; sk.split = sp; }
+    }
   }
   if (sk.split == 1) sk.full_items = slots;
   const int n_split_tiles = slots - sk.full_items;

@@ -131,9 +131,9 @@ Layout make_layout(const hero_config& c) {
     L.vtmp_off = w;
     w += L.vt_bytes;
   }
-  // partial sums of GEMM tiles cut along k: at most 256 blocks of 256 x 256 fp32 (large problems only)
+  // partial sums of GEMM tiles cut along k: up to 512 blocks of 256 x 256 fp32 (large problems only)
   L.splitk_off = w;
-  L.splitk_bytes = L.n_tokens >= 2048 ? (size_t)256 * 262144 : 0;
+  L.splitk_bytes = L.n_tokens >= 2048 ? (size_t)512 * 262144 : 0;
   w += L.splitk_bytes;
   L.ws_bytes = w;
   return L;
