@@ -38,6 +38,8 @@ the design notes at the repository root):
     patches are clipped to the grid and sized on their own;
   * Sample(P, R) is deterministic age-priority: within a patch take the n_p
     tokens with the largest (age, hash) key, hash = mix32(seed, step, token);
+    a second, stochastic reading (select_mode 1) draws the n_p tokens without
+    replacement with probability proportional to age + 1;
     selected ages become 0, all others grow by 1, a full step zeroes all ages;
   * the block is pre-LayerNorm with affine parameters, biased Linear layers,
     tanh-form GELU and softmax scale 1/sqrt(head_dim).
@@ -159,19 +161,67 @@ def patch_list(frames: int, height: int, width: int, ph: int, pw: int
     return out
 
 
+SELECT_AGE_PRIORITY = 0     # deterministic: oldest first, hash breaks ties
+SELECT_AGE_WEIGHTED = 1     # stochastic: sampling without replacement, probability ~ age + 1
+
+AGE_WEIGHT_CAP = 0xFFFF     # weights are min(age, cap) + 1 so a patch's total stays below 2^32
+
+
+def draw32(seed: int, step: int, first_token: int, draw: int) -> int:
+    """32-bit random word of draw number `draw` (0-based) in the patch whose first
+    (top-left) token is `first_token`: fmix32(mix32(seed, step, first_token) +
+    0x9E3779B9 * (draw + 1)) modulo 2^32."""
+    base = int(mix32(seed, step, np.array([first_token]))[0])
+    return int(fmix32(np.uint64((base + 0x9E3779B9 * (draw + 1)) & _M32)))
+
+
+def sample_weighted(weights: List[int], n_take: int, words: List[int]) -> List[int]:
+    """Weighted sampling without replacement, one draw at a time (the textbook
+    sequential scheme): with W the total weight of the items not yet taken, draw
+    number j maps its 32-bit word u to r = floor(u * W / 2^32) in [0, W) and takes
+    the first remaining item, in list order, whose running weight sum exceeds r.
+    Returns the taken positions in draw order."""
+    left = list(range(len(weights)))
+    taken = []
+    for j in range(n_take):
+        total = sum(weights[e] for e in left)
+        r = (words[j] * total) >> 32
+        run = 0
+        for e in left:
+            run += weights[e]
+            if run > r:
+                taken.append(e)
+                left.remove(e)
+                break
+    return taken
+
+
 def select(ages: np.ndarray, cfg, step: int) -> Tuple[np.ndarray, np.ndarray]:
-    """S(z) of Eq. 4 with age-priority sampling.
+    """S(z) of Eq. 4 with the frequency-aware tracking of Sec. 3.3.
 
     ages: int32 [n_video] (how many cached steps each token has gone unsampled).
     Returns (idx, new_ages): idx are joint-sequence row indices (n_text + token),
-    ordered patch-major and, inside a patch, by decreasing (age, hash) key.
+    ordered patch-major.  Two readings of "higher sampling probabilities to those
+    neglected longer", chosen by cfg.select_mode (default: age priority):
+      age priority  -- inside a patch the n_p tokens with the largest (age, hash)
+                       key, listed by decreasing key;
+      age weighted  -- n_p draws without replacement with probability
+                       proportional to age + 1 among the tokens still left
+                       (tokens in row-major order inside the patch), listed in
+                       draw order.
     """
     ages = np.asarray(ages, dtype=np.int64)
+    mode = getattr(cfg, "select_mode", SELECT_AGE_PRIORITY)
     sel: List[int] = []
     for (t, y0, x0, hh, ww) in patch_list(cfg.frames, cfg.height, cfg.width, cfg.patch_h, cfg.patch_w):
         toks = np.array([(t * cfg.height + (y0 + dy)) * cfg.width + (x0 + dx)
                          for dy in range(hh) for dx in range(ww)], dtype=np.int64)
         n_p = tokens_per_patch(cfg.ratio, len(toks))
+        if mode == SELECT_AGE_WEIGHTED:
+            weights = [min(int(a), AGE_WEIGHT_CAP) + 1 for a in ages[toks]]
+            words = [draw32(cfg.seed, step, int(toks[0]), j) for j in range(n_p)]
+            sel.extend(int(toks[e]) for e in sample_weighted(weights, n_p, words))
+            continue
         hashes = mix32(cfg.seed, step, toks).astype(np.int64)
         keys = (ages[toks] << 32) | hashes
         order = np.argsort(-keys, kind="stable")  # keys are distinct: hashes are

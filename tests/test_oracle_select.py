@@ -193,6 +193,116 @@ def test_position_rotates_over_consecutive_cached_steps():
     assert (seen == 1).all()       # 2x2 patches, one per step: four steps visit every token once
 
 
+# ---------------------------------------------------------------- age-weighted sampling (second reading of Sec. 3.3)
+
+def exact_inclusion_probabilities(weights, n_take):
+    """Inclusion probability of each item under sequential weighted sampling without
+    replacement, by enumerating every ordered outcome (exact rational arithmetic)."""
+    from fractions import Fraction
+    n = len(weights)
+    incl = [Fraction(0)] * n
+
+    def rec(left, prob, depth):
+        if depth == n_take:
+            for e in range(n):
+                if e not in left:
+                    incl[e] += prob
+            return
+        total = sum(weights[e] for e in left)
+        for e in left:
+            rec(left - {e}, prob * Fraction(weights[e], total), depth + 1)
+    rec(frozenset(range(n)), Fraction(1), 0)
+    return [float(p) for p in incl]
+
+
+def test_sample_weighted_maps_the_random_word_onto_the_running_sums():
+    # weights 1,2,3 -> [0,1) item 0, [1,3) item 1, [3,6) item 2; r = floor(u * 6 / 2^32)
+    w = [1, 2, 3]
+    two32 = 1 << 32
+    assert O.sample_weighted(w, 1, [0]) == [0]
+    assert O.sample_weighted(w, 1, [two32 // 6 - 1]) == [0]
+    assert O.sample_weighted(w, 1, [two32 // 6 + 1]) == [1]
+    assert O.sample_weighted(w, 1, [two32 // 2 - 1]) == [1]
+    assert O.sample_weighted(w, 1, [two32 // 2]) == [2]
+    assert O.sample_weighted(w, 1, [two32 - 1]) == [2]
+    # second draw works on what is left: after taking item 2, total 3: [0,1) item 0, [1,3) item 1
+    assert O.sample_weighted(w, 2, [two32 - 1, 0]) == [2, 0]
+    assert O.sample_weighted(w, 2, [two32 - 1, two32 // 3 + 1]) == [2, 1]
+    assert sorted(O.sample_weighted(w, 3, [5, 7, 11])) == [0, 1, 2]       # taking everything
+
+
+@pytest.mark.parametrize("n_take", [1, 2, 3])
+def test_age_weighted_sampling_follows_the_exact_inclusion_probabilities(n_take):
+    """2x3 patches whose six tokens have ages 0..5 (weights 1..6): the empirical inclusion
+    frequencies over all patches and many steps match the enumerated probabilities of
+    sequential weighted sampling without replacement."""
+    cfg = get_config("paper_point", frames=2, ratio=n_take / 6.0, select_mode=1)
+    assert O.tokens_per_patch(cfg.ratio, 6) == n_take
+    tok = np.arange(cfg.n_video)
+    y, x = (tok % (cfg.height * cfg.width)) // cfg.width, tok % cfg.width
+    pos = (y % 2) * 3 + (x % 3)                       # position inside the 2x3 patch = its age
+    ages = pos.astype(np.int32)
+    counts = np.zeros(6)
+    n_steps = 40
+    for step in range(1, n_steps + 1):
+        idx, _ = O.select(ages, cfg, step)
+        np.add.at(counts, pos[idx.astype(int) - cfg.n_text], 1)
+    n_patches = cfg.n_video // 6
+    freq = counts / (n_patches * n_steps)
+    want = np.array(exact_inclusion_probabilities([1, 2, 3, 4, 5, 6], n_take))
+    assert abs(freq.sum() - n_take) < 1e-9
+    sigma = np.sqrt(want * (1 - want) / (n_patches * n_steps))
+    assert (np.abs(freq - want) < 4.5 * sigma + 1e-12).all(), (freq, want)
+    assert (np.diff(freq) > 0).all()                  # neglected longer => more likely
+
+
+def test_age_weighted_sampling_invariants_and_age_tail():
+    cfg = get_config("tiny", height=7, width=9, patch_h=2, patch_w=3, ratio=0.34, select_mode=1)
+    patches = O.patch_list(cfg.frames, cfg.height, cfg.width, cfg.patch_h, cfg.patch_w)
+    ages = np.zeros(cfg.n_video, np.int32)
+    old = 0
+    for step in range(1, 61):
+        idx, new_ages = O.select(ages, cfg, step)
+        tok = idx.astype(int) - cfg.n_text
+        assert len(np.unique(idx)) == len(idx) and tok.min() >= 0 and tok.max() < cfg.n_video
+        p0 = 0
+        for (t, y0, x0, hh, ww) in patches:
+            n_p = O.tokens_per_patch(cfg.ratio, hh * ww)
+            for tk in tok[p0:p0 + n_p]:
+                tt, rem = divmod(tk, cfg.height * cfg.width)
+                yy, xx = divmod(rem, cfg.width)
+                assert tt == t and y0 <= yy < y0 + hh and x0 <= xx < x0 + ww
+            p0 += n_p
+        assert p0 == len(idx)
+        want = ages + 1
+        want[tok] = 0
+        np.testing.assert_array_equal(new_ages, want)
+        ages = new_ages
+        if step > 20:
+            old += int((ages >= 9).sum())
+    # 2 of 6 per step: age-blind sampling leaves (2/3)^9 = 2.6 % of the tokens older than 8 steps;
+    # weighting by age + 1 makes that far rarer
+    assert old / (40 * cfg.n_video) < 0.004
+    a, _ = O.select(np.zeros(cfg.n_video, np.int32), cfg, 5)
+    b, _ = O.select(np.zeros(cfg.n_video, np.int32), cfg, 5)
+    c, _ = O.select(np.zeros(cfg.n_video, np.int32), cfg.with_(seed=77), 5)
+    np.testing.assert_array_equal(a, b)
+    assert not np.array_equal(a, c)
+
+
+def test_age_weighted_degenerate_cases():
+    cfg = get_config("tiny", select_mode=1)
+    idx, ages = O.select(np.full(cfg.n_video, 3, np.int32), cfg.with_(ratio=1.0), 2)
+    assert sorted(idx.tolist()) == list(range(cfg.n_text, cfg.n_tokens)) and (ages == 0).all()
+    idx, ages = O.select(np.full(cfg.n_video, 3, np.int32), cfg.with_(ratio=0.0), 2)
+    assert len(idx) == 0 and (ages == 4).all()
+    # one token overwhelmingly old: it is taken (weight 65536 against three of weight 1)
+    a0 = np.zeros(cfg.n_video, np.int32)
+    a0[5] = 10 ** 6
+    hits = sum(int(cfg.n_text + 5 in O.select(a0, cfg, s)[0]) for s in range(1, 41))
+    assert hits >= 39
+
+
 # ---------------------------------------------------------------- cost model (Tables 1, 3, 4)
 
 def test_cost_model_matches_paper_flops_structure():

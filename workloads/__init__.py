@@ -52,6 +52,7 @@ class HeroConfig:
     ln_eps: float = 1e-5
     seed: int = 1234          # selection seed
     resid_fp32: bool = True   # residual stream x kept in fp32 on the GPU
+    select_mode: int = 0      # 0: age-priority selection, 1: age-weighted random sampling (Sec. 3.3)
 
     @property
     def n_video(self) -> int:
