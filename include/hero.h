@@ -47,6 +47,11 @@ enum {
 };
 
 enum { HERO_DTYPE_BF16 = 0, HERO_DTYPE_FP32 = 1 };
+/* Sample(P, R) of Eq. 4 under the frequency-aware tracking of Sec. 3.3, two readings:
+ * AGE_PRIORITY: the n_p tokens of a patch with the largest (age, hash) key, listed by decreasing key;
+ * AGE_WEIGHTED: n_p draws without replacement, probability proportional to min(age, 65535) + 1 among
+ * the tokens still left (row-major order inside the patch), listed in draw order. */
+enum { HERO_SELECT_AGE_PRIORITY = 0, HERO_SELECT_AGE_WEIGHTED = 1 };
 
 /* Plain-data configuration, copied at hero_cache_create(). */
 typedef struct hero_config {
@@ -64,6 +69,8 @@ typedef struct hero_config {
   int32_t resid_dtype; /* dtype of x: HERO_DTYPE_FP32 or HERO_DTYPE_BF16                 */
   float   ln_eps;
   uint64_t seed;       /* selection seed                                                 */
+  int32_t select_mode; /* HERO_SELECT_AGE_PRIORITY or HERO_SELECT_AGE_WEIGHTED (Sec. 3.3 tracking) */
+  int32_t reserved;    /* must be 0                                                      */
 } hero_config;
 
 /* Borrowed device pointers to one block's parameters (bf16). */
@@ -109,8 +116,8 @@ int hero_set_layer_weights(hero_cache_t c, int32_t layer, const hero_layer_weigh
 int hero_full_layer(hero_cache_t c, int32_t layer, void* dev_x, void* stream);
 
 /* S(z) of Eq. 4 with frequency-aware tracking (Sec. 3.3): writes n_sel row
- * indices (int32, joint-sequence rows, patch-major, decreasing priority inside
- * a patch) to dev_idx and updates the token ages.  n_sel_host (optional)
+ * indices (int32, joint-sequence rows, patch-major, inside a patch in the order
+ * of the configured select_mode) to dev_idx and updates the token ages.  n_sel_host (optional)
  * receives the count, which depends on the configuration only. */
 int hero_select(hero_cache_t c, int32_t step, int32_t* dev_idx, int32_t* n_sel_host, void* stream);
 

@@ -53,7 +53,8 @@ class hero_config(Structure):
                 ("hidden", c_int32), ("n_heads", c_int32), ("head_dim", c_int32), ("ffn_dim", c_int32),
                 ("frames", c_int32), ("height", c_int32), ("width", c_int32), ("n_text", c_int32),
                 ("patch_h", c_int32), ("patch_w", c_int32), ("ratio", c_float),
-                ("resid_dtype", c_int32), ("ln_eps", c_float), ("seed", c_uint64)]
+                ("resid_dtype", c_int32), ("ln_eps", c_float), ("seed", c_uint64),
+                ("select_mode", c_int32), ("reserved", c_int32)]
 
 
 class hero_layer_weights(Structure):
@@ -118,7 +119,8 @@ def make_config(cfg, resid_fp32: Optional[bool] = None) -> hero_config:
     rf = cfg.resid_fp32 if resid_fp32 is None else resid_fp32
     return hero_config(cfg.n_layers, cfg.n_shallow, cfg.interval, cfg.hidden, cfg.n_heads, cfg.head_dim,
                        cfg.ffn_dim, cfg.frames, cfg.height, cfg.width, cfg.n_text, cfg.patch_h, cfg.patch_w,
-                       cfg.ratio, DTYPE_FP32 if rf else DTYPE_BF16, cfg.ln_eps, cfg.seed)
+                       cfg.ratio, DTYPE_FP32 if rf else DTYPE_BF16, cfg.ln_eps, cfg.seed,
+                       getattr(cfg, "select_mode", 0), 0)
 
 
 def _stream() -> c_void_p:

@@ -60,6 +60,11 @@ int check_config(const hero_config* c) {
   if (c->resid_dtype != HERO_DTYPE_FP32 && c->resid_dtype != HERO_DTYPE_BF16)
     return fail(HERO_ERR_INVALID_ARG, "resid_dtype must be HERO_DTYPE_FP32 or HERO_DTYPE_BF16");
   if (!(c->ratio >= 0.f) || !(c->ln_eps >= 0.f)) return fail(HERO_ERR_INVALID_ARG, "ratio and ln_eps must be >= 0");
+  if (c->select_mode != HERO_SELECT_AGE_PRIORITY && c->select_mode != HERO_SELECT_AGE_WEIGHTED)
+    return fail(HERO_ERR_INVALID_ARG, "select_mode must be HERO_SELECT_AGE_PRIORITY or HERO_SELECT_AGE_WEIGHTED");
+  if (c->select_mode == HERO_SELECT_AGE_WEIGHTED && (int64_t)c->patch_h * c->patch_w > 65535)
+    return fail(HERO_ERR_SHAPE, "age-weighted selection needs patches of at most 65535 tokens");
+  if (c->reserved != 0) return fail(HERO_ERR_INVALID_ARG, "reserved must be 0");
   if (c->head_dim != 32 && c->head_dim != 64) return fail(HERO_ERR_SHAPE, "head_dim must be 32 or 64");
   if (c->hidden != c->n_heads * c->head_dim || c->n_heads < 1)
     return fail(HERO_ERR_SHAPE, "hidden must equal n_heads * head_dim");
@@ -498,7 +503,7 @@ int hero_select(hero_cache_t c, int32_t step, int32_t* dev_idx, int32_t* n_sel_h
   uint32_t s0 = (uint32_t)seed ^ (uint32_t)(seed >> 32);
   uint32_t salt = fmix32_host(s0 + 0x9E3779B9u * ((uint32_t)step + 1u));
   PROF_LAUNCH(c, HERO_PROF_SELECT, 8.0 * c->lay.n_video + 4.0 * c->geom.n_sel, (hipStream_t)stream,
-              launch_select(c->geom, salt, c->ages, dev_idx, (hipStream_t)stream));
+              launch_select(c->geom, c->cfg.select_mode, salt, c->ages, dev_idx, (hipStream_t)stream));
   if (n_sel_host) *n_sel_host = c->geom.n_sel;
   return HERO_OK;
 }

@@ -19,7 +19,9 @@ struct SelectGeom {
 };
 
 hipError_t launch_fill_i32(int32_t* p, int32_t v, int64_t n, hipStream_t st);
-hipError_t launch_select(const SelectGeom& g, uint32_t step_salt, int32_t* ages, int32_t* idx, hipStream_t st);
+// mode 0: age priority (largest (age, hash) keys); mode 1: age-weighted sampling without replacement
+hipError_t launch_select(const SelectGeom& g, int mode, uint32_t step_salt, int32_t* ages, int32_t* idx,
+                         hipStream_t st);
 hipError_t launch_gather_ln(const void* x, bool x_fp32, const bf16_t* add, const int32_t* rows, int n_rows,
                             int hidden, const bf16_t* gain, const bf16_t* bias, float eps, bf16_t* out,
                             hipStream_t st);

@@ -71,10 +71,68 @@ __global__ void select_kernel(SelectGeom g, uint32_t step_salt, int32_t* __restr
   }
 }
 
-hipError_t launch_select(const SelectGeom& g, uint32_t step_salt, int32_t* ages, int32_t* idx, hipStream_t st) {
+// Age-weighted reading of the frequency-aware tracking (Sec. 3.3): n_p draws without replacement,
+// each taking a token with probability proportional to min(age, 65535) + 1 among those left.
+// Draw j of a patch uses the word u = fmix32(hash(first token of the patch) + 0x9E3779B9 * (j+1)),
+// maps it to r = floor(u * W / 2^32) with W the weight still left, and takes the first remaining
+// token, in row-major order, whose running weight sum exceeds r.  Taken tokens are marked by a
+// negative age until the final pass writes the new ages (a patch belongs to one thread).
+__global__ void select_weighted_kernel(SelectGeom g, uint32_t step_salt, int32_t* ages, int32_t* __restrict__ idx) {
+  int p = blockIdx.x * blockDim.x + threadIdx.x;
+  if (p >= g.n_patches) return;
+  int per_frame = g.grid_h * g.grid_w;
+  int t = p / per_frame;
+  int rem = p - t * per_frame;
+  int py = rem / g.grid_w;
+  int px = rem - py * g.grid_w;
+  int y0 = py * g.patch_h, x0 = px * g.patch_w;
+  int hh = min(g.patch_h, g.height - y0);
+  int ww = min(g.patch_w, g.width - x0);
+  bool last_row = (py == g.grid_h - 1), last_col = (px == g.grid_w - 1);
+  int cls_row = last_row ? 1 : 0;
+  int n_p = g.n_take[cls_row * 2 + (last_col ? 1 : 0)];
+  int out = t * g.take_per_frame + py * g.take_per_full_row + px * g.n_take[cls_row * 2];
+  int size = hh * ww;
+  int first_tok = (t * g.height + y0) * g.width + x0;
+  uint32_t base = fmix32(step_salt ^ ((uint32_t)first_tok * 0x85EBCA6Bu));
+  uint32_t total = 0;
+  for (int e = 0; e < size; ++e) {
+    int dy = e / ww, dx = e - dy * ww;
+    total += (uint32_t)min(ages[first_tok + dy * g.width + dx], 0xFFFF) + 1u;
+  }
+  for (int j = 0; j < n_p; ++j) {
+    uint32_t u = fmix32(base + 0x9E3779B9u * (uint32_t)(j + 1));
+    uint32_t r = (uint32_t)(((uint64_t)u * total) >> 32);
+    uint32_t run = 0;
+    for (int e = 0; e < size; ++e) {
+      int dy = e / ww, dx = e - dy * ww;
+      int tok = first_tok + dy * g.width + dx;
+      int32_t a = ages[tok];
+      if (a < 0) continue;
+      uint32_t w = (uint32_t)min(a, 0xFFFF) + 1u;
+      run += w;
+      if (run > r) {
+        idx[out + j] = g.n_text + tok;
+        ages[tok] = -1;
+        total -= w;
+        break;
+      }
+    }
+  }
+  for (int e = 0; e < size; ++e) {
+    int dy = e / ww, dx = e - dy * ww;
+    int tok = first_tok + dy * g.width + dx;
+    int32_t a = ages[tok];
+    ages[tok] = a < 0 ? 0 : a + 1;
+  }
+}
+
+hipError_t launch_select(const SelectGeom& g, int mode, uint32_t step_salt, int32_t* ages, int32_t* idx,
+                         hipStream_t st) {
   if (g.n_patches <= 0) return hipSuccess;
   int blocks = (g.n_patches + 127) / 128;
-  hipLaunchKernelGGL(select_kernel, dim3(blocks), dim3(128), 0, st, g, step_salt, ages, idx);
+  if (mode == 1) hipLaunchKernelGGL(select_weighted_kernel, dim3(blocks), dim3(128), 0, st, g, step_salt, ages, idx);
+  else hipLaunchKernelGGL(select_kernel, dim3(blocks), dim3(128), 0, st, g, step_salt, ages, idx);
   return hipGetLastError();
 }
 

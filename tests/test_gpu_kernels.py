@@ -34,6 +34,16 @@ def rnd(seed, *shape, scale=1.0):
     ("cvx2b_block", dict(hidden=64, n_heads=1, ffn_dim=64)),     # the real 13x30x45 grid, 2x2 clipped at x=44
     ("cvx2b_block", dict(hidden=64, n_heads=1, ffn_dim=64, patch_h=2, patch_w=5, ratio=0.1)),
     ("paper_point", dict(hidden=64, n_heads=1, ffn_dim=64, n_layers=1, n_shallow=1)),
+    # age-weighted sampling without replacement (second reading of the tracking paragraph)
+    ("tiny", dict(select_mode=1)),
+    ("tiny", dict(select_mode=1, height=7, width=9, patch_h=2, patch_w=3, ratio=0.34)),
+    ("tiny", dict(select_mode=1, frames=2, height=5, width=5, patch_h=3, patch_w=2, ratio=0.5, seed=(7 << 32) | 99)),
+    ("tiny", dict(select_mode=1, ratio=1.0)),
+    ("tiny", dict(select_mode=1, ratio=0.0)),
+    ("tiny", dict(select_mode=1, patch_h=64, patch_w=64, ratio=0.3)),     # one clipped 8x8 patch per frame
+    ("cvx2b_block", dict(select_mode=1, hidden=64, n_heads=1, ffn_dim=64)),
+    ("paper_point", dict(select_mode=1, hidden=64, n_heads=1, ffn_dim=64, n_layers=1, n_shallow=1)),
+    ("paper_point", dict(select_mode=1, hidden=64, n_heads=1, ffn_dim=64, n_layers=1, n_shallow=1, ratio=0.5)),
 ])
 def test_select_bit_exact(name, over):
     cfg = get_config(name, **over)

@@ -243,6 +243,8 @@ def test_special_schedules():
     run_schedule(get_config("tiny", n_shallow=0, interval=2), 0.05, 5)
     run_schedule(get_config("tiny", n_shallow=2, interval=3), 0.05, 5)
     run_schedule(get_config("tiny", interval=1), 0.05, 3)
+    say("age-weighted random selection through the whole schedule")
+    run_schedule(get_config("tiny", select_mode=1, interval=5, patch_w=3, ratio=0.34), 0.05, 10)
 
 
 def test_deep_stack_in_one_pass_matches_per_layer_extrapolation():

@@ -37,9 +37,10 @@ def test_every_declared_symbol_is_exported_and_bound(lib):
 
 
 def test_config_struct_layout_matches_header(lib):
-    # 15 int32/float fields then a uint64 seed: 16-field struct of 72 bytes with natural alignment
-    assert ctypes.sizeof(B.hero_config) == 72
+    # 16 int32/float fields, a uint64 seed, then select_mode and a reserved word: 80 bytes
+    assert ctypes.sizeof(B.hero_config) == 80
     assert B.hero_config.seed.offset == 64
+    assert B.hero_config.select_mode.offset == 72
     assert ctypes.sizeof(B.hero_layer_weights) == 12 * ctypes.sizeof(ctypes.c_void_p)
 
 
@@ -85,6 +86,9 @@ def test_invalid_configs_are_rejected(lib):
     assert rc_of(interval=0) == B.HERO_ERR_INVALID_ARG
     assert rc_of(patch_h=0) == B.HERO_ERR_INVALID_ARG
     assert rc_of(ratio=-0.5) == B.HERO_ERR_INVALID_ARG
+    assert rc_of(select_mode=2) == B.HERO_ERR_INVALID_ARG
+    assert rc_of(select_mode=1) == B.HERO_OK
+    assert rc_of(select_mode=1, height=300, width=300, patch_h=256, patch_w=257) == B.HERO_ERR_SHAPE
     assert rc_of(head_dim=48, n_heads=4, hidden=192) == B.HERO_ERR_SHAPE
     assert rc_of(hidden=96, n_heads=3) == B.HERO_ERR_SHAPE           # not a multiple of 64
     assert rc_of(hidden=128, n_heads=3) == B.HERO_ERR_SHAPE          # hidden != heads * head_dim
