@@ -23,6 +23,8 @@ the paper's order and notation:
   select            Eq. 4 (patch-wise sampling) with the frequency-aware
                     tracking paragraph of Sec. 3.3.
   HeroOracle.step   Alg. 1's outer loops.
+  second_difference_variance / stability_scores
+                    the per-layer stability score of Sec. 3.2's feature analysis.
 
 Readings taken where the paper is silent or inconsistent (each is listed in
 the design notes at the repository root):
@@ -40,6 +42,8 @@ the design notes at the repository root):
     tokens with the largest (age, hash) key, hash = mix32(seed, step, token);
     a second, stochastic reading (select_mode 1) draws the n_p tokens without
     replacement with probability proportional to age + 1;
+  * stability score: population variance of F_{t+1} - 2 F_t + F_{t-1} over all
+    elements and steps, then 1 - (v - min) / (max - min) across layers;
     selected ages become 0, all others grow by 1, a full step zeroes all ages;
   * the block is pre-LayerNorm with affine parameters, biased Linear layers,
     tanh-form GELU and softmax scale 1/sqrt(head_dim).
@@ -371,6 +375,34 @@ class HeroOracle:
             else:
                 x = self.extrapolate_layer(l, x, k)
         return x
+
+
+# ----------------------------------------------------------------------------
+# stability score (Sec. 3.2, hierarchical feature analysis)
+# ----------------------------------------------------------------------------
+
+def second_difference_variance(features: List[np.ndarray]) -> float:
+    """Variance of the second-order temporal differences of one layer's features.
+
+    features: the layer's feature at T >= 3 consecutive (full) steps, equal shapes.
+    D_t = F_{t+1} - 2 F_t + F_{t-1} for t = 1..T-2; the variance is taken over all
+    elements of all D_t together (population variance, float64)."""
+    f = [np.asarray(a, dtype=np.float64) for a in features]
+    if len(f) < 3:
+        raise ValueError("need at least three steps")
+    d = np.concatenate([(f[t + 1] - 2.0 * f[t] + f[t - 1]).ravel() for t in range(1, len(f) - 1)])
+    return float(np.mean((d - d.mean()) ** 2))
+
+
+def stability_scores(variances) -> np.ndarray:
+    """Per-layer variances -> scores in [0, 1], higher = more stable: min-max
+    normalisation, inverted (the steadiest layer scores 1, the most variable 0;
+    all equal -> all 1)."""
+    v = np.asarray(variances, dtype=np.float64)
+    lo, hi = v.min(), v.max()
+    if hi == lo:
+        return np.ones_like(v)
+    return 1.0 - (v - lo) / (hi - lo)
 
 
 # ----------------------------------------------------------------------------

@@ -162,3 +162,41 @@ def test_block_forward_matches_library_block():
     np.testing.assert_allclose(y, (a + gf).numpy(), rtol=1e-9, atol=1e-11)
     np.testing.assert_allclose(k, k_.numpy(), rtol=1e-10, atol=1e-12)
     np.testing.assert_allclose(v, v_.numpy(), rtol=1e-10, atol=1e-12)
+
+
+# ---------------------------------------------------------------- stability score (Sec. 3.2)
+
+def test_second_difference_variance_closed_forms():
+    rng = np.random.default_rng(3)
+    a, b, c = rng.standard_normal((3, 40, 16))
+    # linear in time: second differences vanish
+    lin = [a + b * t for t in range(5)]
+    assert O.second_difference_variance(lin) < 1e-24
+    # quadratic in time: D = 2c at every step, so the variance is Var(2c) over the elements
+    quad = [a + b * t + c * t * t for t in range(6)]
+    np.testing.assert_allclose(O.second_difference_variance(quad), np.var(2.0 * c), rtol=1e-10)
+    # the same quadratic with one coefficient for all elements: D is constant, variance 0
+    quad1 = [a + b * t + 0.7 * t * t for t in range(4)]
+    assert O.second_difference_variance(quad1) < 1e-20
+    # hand-computed: features 0, 1, 4, 4 on two elements (second element doubled)
+    f = [np.array([0.0, 0.0]), np.array([1.0, 2.0]), np.array([4.0, 8.0]), np.array([4.0, 8.0])]
+    # D_1 = (2, 4), D_2 = (-3, -6): mean -0.75, variance = mean of squares - mean^2
+    d = np.array([2.0, 4.0, -3.0, -6.0])
+    np.testing.assert_allclose(O.second_difference_variance(f), np.mean(d * d) - d.mean() ** 2, rtol=1e-12)
+    with pytest.raises(ValueError):
+        O.second_difference_variance(f[:2])
+
+
+def test_second_difference_variance_of_white_noise_is_six_sigma_squared():
+    rng = np.random.default_rng(4)
+    sigma = 0.3
+    feats = [sigma * rng.standard_normal(200000) for _ in range(3)]
+    # Var(F2 - 2 F1 + F0) = (1 + 4 + 1) sigma^2 for independent steps
+    np.testing.assert_allclose(O.second_difference_variance(feats), 6 * sigma ** 2, rtol=0.02)
+
+
+def test_stability_scores_normalise_and_invert():
+    s = O.stability_scores([4.0, 1.0, 2.5, 1.0])
+    np.testing.assert_allclose(s, [0.0, 1.0, 0.5, 1.0])
+    np.testing.assert_allclose(O.stability_scores([3.0, 3.0]), [1.0, 1.0])
+    assert s.min() == 0.0 and s.max() == 1.0
