@@ -213,6 +213,22 @@ int hero_attention(const void* dev_q, const void* dev_k, const void* dev_vt, int
 int hero_axpy_features(void* dev_x, int32_t x_dtype, const void* s_cur, const void* s_prev,
                        float alpha, int64_t n_elems, void* stream);
 
+/* ---- stability analysis (Sec. 3.2: which layers are steady enough to extrapolate) ---- */
+
+/* Second-order temporal difference of one layer's feature, D = f_next - 2 f_cur + f_prev, over
+ * n_elems bf16 elements (device arrays, n_elems % 8 == 0): dev_stats[0] (+)= sum D, dev_stats[1]
+ * (+)= sum D^2, in fp64, with a fixed summation order (reproducible).  accumulate != 0 adds to
+ * what dev_stats holds (for more than three steps), else overwrites.  dev_scratch: caller-owned
+ * device memory of at least 16 KiB, 8-byte aligned; calls sharing it must not overlap.
+ * The variance of Sec. 3.2 is stats[1]/n - (stats[0]/n)^2 with n the number of elements summed. */
+int hero_second_diff_stats(const void* f_prev, const void* f_cur, const void* f_next, int64_t n_elems,
+                           void* dev_scratch, size_t scratch_bytes, double* dev_stats, int32_t accumulate,
+                           void* stream);
+
+/* Host only: per-layer variances -> stability scores in [0, 1], higher = steadier
+ * (1 - (v - min) / (max - min); all equal -> 1). */
+int hero_stability_scores(const double* variances, int32_t n_layers, double* scores);
+
 #ifdef __cplusplus
 }
 #endif

@@ -38,7 +38,7 @@ EXPORTS = (
     "hero_select", "hero_reset_ages", "hero_refresh_layer", "hero_extrapolate_layer", "hero_step",
     "hero_cache_view", "hero_cache_state", "hero_profile_begin", "hero_profile_begin_kinds", "hero_profile_end", "hero_gather_ln", "hero_linear", "hero_linear_scratch",
     "hero_attention",
-    "hero_axpy_features",
+    "hero_axpy_features", "hero_second_diff_stats", "hero_stability_scores",
 )
 
 
@@ -99,6 +99,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
         "hero_linear_scratch": [P, P, P, P, I, I, I, I, P, ctypes.c_size_t, P],
         "hero_attention": [P, P, P, c_int64, P, I, I, I, I, P],
         "hero_axpy_features": [P, I, P, P, c_float, c_int64, P],
+        "hero_second_diff_stats": [P, P, P, c_int64, P, ctypes.c_size_t, P, I, P],
+        "hero_stability_scores": [POINTER(ctypes.c_double), I, POINTER(ctypes.c_double)],
     }
     for name, argtypes in sig.items():
         fn = getattr(lib, name)
@@ -343,3 +345,25 @@ def hero_axpy_features(x, s_cur, s_prev, alpha: float):
         raise ValueError("shape mismatch")
     _check(load_library().hero_axpy_features(_ptr(x), _dtype_code(x), _ptr(s_cur), _ptr(s_prev), alpha,
                                              x.numel(), _stream()))
+
+
+def hero_second_diff_stats(f_prev, f_cur, f_next, scratch, stats, accumulate: bool = False):
+    """stats (float64[2] device tensor) (+)= [sum D, sum D^2] with D = f_next - 2 f_cur + f_prev."""
+    import torch
+    for t, n in ((f_prev, "f_prev"), (f_cur, "f_cur"), (f_next, "f_next")):
+        _need(t, torch.bfloat16, n)
+    if f_prev.numel() != f_cur.numel() or f_next.numel() != f_cur.numel():
+        raise ValueError("shape mismatch")
+    if stats.dtype != torch.float64 or stats.numel() < 2 or not stats.is_cuda or not scratch.is_cuda:
+        raise ValueError("stats must be a float64 device tensor of 2 elements, scratch a device tensor")
+    _check(load_library().hero_second_diff_stats(_ptr(f_prev), _ptr(f_cur), _ptr(f_next), f_cur.numel(), _ptr(scratch),
+                                                 scratch.numel() * scratch.element_size(), _ptr(stats),
+                                                 1 if accumulate else 0, _stream()))
+
+
+def hero_stability_scores(variances):
+    n = len(variances)
+    v = (ctypes.c_double * n)(*[float(a) for a in variances])
+    out = (ctypes.c_double * n)()
+    _check(load_library().hero_stability_scores(v, n, out))
+    return list(out)

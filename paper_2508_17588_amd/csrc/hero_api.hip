@@ -702,4 +702,30 @@ int hero_axpy_features(void* dev_x, int32_t x_dtype, const void* s_cur, const vo
   return HERO_OK;
 }
 
+int hero_second_diff_stats(const void* f_prev, const void* f_cur, const void* f_next, int64_t n_elems,
+                           void* dev_scratch, size_t scratch_bytes, double* dev_stats, int32_t accumulate,
+                           void* stream) {
+  if (!f_prev || !f_cur || !f_next || !dev_scratch || !dev_stats) return fail(HERO_ERR_INVALID_ARG, "null pointer");
+  if (n_elems < 0 || n_elems % 8 != 0) return fail(HERO_ERR_SHAPE, "n_elems must be a non-negative multiple of 8");
+  if (scratch_bytes < second_diff_scratch_bytes())
+    return fail(HERO_ERR_BUFFER_TOO_SMALL, "scratch has %zu bytes, %zu needed", scratch_bytes, second_diff_scratch_bytes());
+  if ((uintptr_t)dev_scratch % 8 != 0 || (uintptr_t)dev_stats % 8 != 0)
+    return fail(HERO_ERR_INVALID_ARG, "scratch and stats must be 8-byte aligned");
+  HIP_TRY(launch_second_diff_stats((const bf16_t*)f_prev, (const bf16_t*)f_cur, (const bf16_t*)f_next, n_elems,
+                                   (double*)dev_scratch, dev_stats, accumulate != 0, (hipStream_t)stream));
+  return HERO_OK;
+}
+
+int hero_stability_scores(const double* variances, int32_t n_layers, double* scores) {
+  if (!variances || !scores || n_layers < 1) return fail(HERO_ERR_INVALID_ARG, "bad arguments");
+  double lo = variances[0], hi = variances[0];
+  for (int i = 0; i < n_layers; ++i) {
+    if (!(variances[i] >= 0.0)) return fail(HERO_ERR_INVALID_ARG, "variance %d is negative or not a number", i);
+    lo = variances[i] < lo ? variances[i] : lo;
+    hi = variances[i] > hi ? variances[i] : hi;
+  }
+  for (int i = 0; i < n_layers; ++i) scores[i] = hi == lo ? 1.0 : 1.0 - (variances[i] - lo) / (hi - lo);
+  return HERO_OK;
+}
+
 }  // extern "C"

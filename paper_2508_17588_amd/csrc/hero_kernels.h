@@ -47,6 +47,11 @@ enum GemmEpilogue {
   EPI_SCATTER_ADD = 4   // S[row(m), n] += .
 };
 
+// sums of D and D^2, D = f_next - 2 f_cur + f_prev (fp64), into stats[0..1]; scratch: second_diff_scratch_bytes()
+size_t second_diff_scratch_bytes();
+hipError_t launch_second_diff_stats(const bf16_t* f_prev, const bf16_t* f_cur, const bf16_t* f_next, int64_t n_elems,
+                                    double* scratch, double* stats, bool accumulate, hipStream_t st);
+
 struct GemmArgs {
   const bf16_t* a;      // [M, K] row-major
   const bf16_t* w;      // [N, K] row-major

@@ -343,3 +343,70 @@ hipError_t launch_apply_sums(void* x, bool x_fp32, const float* t_cur, const flo
 #undef LAUNCH
   return hipGetLastError();
 }
+
+// ---------------------------------------------------------------------------------
+// Stability analysis (Sec. 3.2): sums of D and D^2 over all elements, where
+// D = F_{t+1} - 2 F_t + F_{t-1} is the second-order temporal difference of a layer's feature.
+// Fixed launch shape and fixed summation order, so the result is reproducible: 1024 workgroups
+// leave one (sum, sum of squares) pair each, a single wave adds the pairs up.  All in fp64.
+// ---------------------------------------------------------------------------------
+constexpr int STAB_BLOCKS = 1024;
+
+__device__ __forceinline__ double wave_sum_f64(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+__global__ __launch_bounds__(256) void second_diff_partial_kernel(
+    const bf16_t* __restrict__ f_prev, const bf16_t* __restrict__ f_cur, const bf16_t* __restrict__ f_next,
+    int64_t n_chunks, double* __restrict__ partial) {
+  __shared__ double red[2][4];
+  double s1 = 0.0, s2 = 0.0;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; c < n_chunks; c += stride) {
+    float a[8], b[8], e[8];
+    load8_stream(f_prev + c * 8, a);
+    load8_stream(f_cur + c * 8, b);
+    load8_stream(f_next + c * 8, e);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const double d = (double)e[j] - 2.0 * (double)b[j] + (double)a[j];
+      s1 += d;
+      s2 += d * d;
+    }
+  }
+  s1 = wave_sum_f64(s1);
+  s2 = wave_sum_f64(s2);
+  const int wave = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) { red[0][wave] = s1; red[1][wave] = s2; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    partial[2 * blockIdx.x] = (red[0][0] + red[0][1]) + (red[0][2] + red[0][3]);
+    partial[2 * blockIdx.x + 1] = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
+  }
+}
+
+__global__ __launch_bounds__(64) void second_diff_final_kernel(const double* __restrict__ partial, int n_blocks,
+                                                               double* __restrict__ stats, int accumulate) {
+  double s1 = 0.0, s2 = 0.0;
+  for (int b = threadIdx.x; b < n_blocks; b += 64) { s1 += partial[2 * b]; s2 += partial[2 * b + 1]; }
+  s1 = wave_sum_f64(s1);
+  s2 = wave_sum_f64(s2);
+  if (threadIdx.x == 0) {
+    stats[0] = (accumulate ? stats[0] : 0.0) + s1;
+    stats[1] = (accumulate ? stats[1] : 0.0) + s2;
+  }
+}
+
+size_t second_diff_scratch_bytes() { return (size_t)STAB_BLOCKS * 2 * sizeof(double); }
+
+hipError_t launch_second_diff_stats(const bf16_t* f_prev, const bf16_t* f_cur, const bf16_t* f_next, int64_t n_elems,
+                                    double* scratch, double* stats, bool accumulate, hipStream_t st) {
+  const int64_t n_chunks = n_elems / 8;
+  hipLaunchKernelGGL(second_diff_partial_kernel, dim3(STAB_BLOCKS), dim3(256), 0, st, f_prev, f_cur, f_next, n_chunks,
+                     scratch);
+  hipLaunchKernelGGL(second_diff_final_kernel, dim3(1), dim3(64), 0, st, scratch, STAB_BLOCKS, stats,
+                     accumulate ? 1 : 0);
+  return hipGetLastError();
+}

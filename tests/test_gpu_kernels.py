@@ -221,3 +221,25 @@ def test_axpy_features(x_dtype):
     torch.cuda.synchronize()
     want = g(8).astype(np.float64) + (g(8).astype(np.float64) - g(4).astype(np.float64)) * 0.75
     np.testing.assert_allclose(to_host_f64(xd), want, rtol=0, atol=1e-6)
+
+
+# ---------------------------------------------------------------- stability statistics (Sec. 3.2)
+
+@pytest.mark.parametrize("n,steps", [(8, 3), (4096 + 8, 3), (300 * 1920, 5), (17776 * 3072, 3)])
+def test_second_diff_stats(n, steps):
+    say(f"second-difference statistics n={n} steps={steps}")
+    rng = np.random.default_rng(21)
+    feats = [round_to_bf16((rng.standard_normal(n) * (0.5 + 0.2 * t)).astype(np.float32)) for t in range(steps)]
+    dev = [to_dev_bf16(f) for f in feats]
+    scratch = torch.empty(2048, dtype=torch.float64, device="cuda")
+    stats = torch.full((2,), 123.0, dtype=torch.float64, device="cuda")
+    for t in range(1, steps - 1):
+        B.hero_second_diff_stats(dev[t - 1], dev[t], dev[t + 1], scratch, stats, accumulate=(t > 1))
+    torch.cuda.synchronize()
+    s1, s2 = stats.cpu().numpy()
+    d = np.concatenate([feats[t + 1].astype(np.float64) - 2.0 * feats[t] + feats[t - 1] for t in range(1, steps - 1)])
+    assert abs(s1 - d.sum()) <= 1e-11 * np.abs(d).sum()
+    assert abs(s2 - (d * d).sum()) <= 1e-11 * (d * d).sum()
+    cnt = d.size
+    var = s2 / cnt - (s1 / cnt) ** 2
+    np.testing.assert_allclose(var, O.second_difference_variance(feats), rtol=1e-9)

@@ -283,3 +283,46 @@ def test_deep_stack_in_one_pass_matches_per_layer_extrapolation():
     cached_step_both_ways(9, 1, "after partial re-fill")
     cached_step_both_ways(10, 2, "after partial re-fill, second cached step")
     cache.close()
+
+
+def test_stability_scores_from_a_runs_own_caches():
+    """Sec. 3.2's analysis on the features a run caches: four full steps of a 4-layer DiT, the
+    stored feature of every layer snapshotted after each, second-difference statistics on the
+    GPU, scores from the library's host function -- against the oracle's own caches and score."""
+    cfg = get_config("tiny", n_layers=4, n_shallow=2, interval=1)
+    say("stability scores over 4 full steps, 4 layers")
+    cache, orc = make(cfg, 0.05)
+    x0 = make_tokens(cfg, seed=1)
+    xo, xd = x0.astype(np.float64), dev_x(x0)
+    text0_np, text0_d = xo[:cfg.n_text].copy(), xd[:cfg.n_text].clone()
+    snaps_d = [[] for _ in range(cfg.n_layers)]
+    snaps_o = [[] for _ in range(cfg.n_layers)]
+    n_steps = 4
+    for step in range(n_steps):
+        x_in_d = xd.clone()
+        cache.hero_step(xd, step)
+        yo = orc.step(xo, step)
+        for l in range(cfg.n_layers):
+            snaps_d[l].append(cache.hero_cache_view(l, B.VIEW_S_CUR).clone())
+            snaps_o[l].append(orc.caches[l].g_attn + orc.caches[l].g_ffn)
+        xd = euler_update(x_in_d, xd, text0_d, cfg.n_text, n_steps)
+        xo = euler_update(xo, yo, text0_np, cfg.n_text, n_steps)
+    scratch = torch.empty(2048, dtype=torch.float64, device="cuda")
+    stats = torch.zeros(2, dtype=torch.float64, device="cuda")
+    var_gpu, var_gpu_inputs, var_orc = [], [], []
+    for l in range(cfg.n_layers):
+        for t in range(1, n_steps - 1):
+            B.hero_second_diff_stats(snaps_d[l][t - 1], snaps_d[l][t], snaps_d[l][t + 1], scratch, stats,
+                                     accumulate=(t > 1))
+        torch.cuda.synchronize()
+        s1, s2 = stats.cpu().numpy()
+        cnt = (n_steps - 2) * snaps_d[l][0].numel()
+        var_gpu.append(s2 / cnt - (s1 / cnt) ** 2)
+        # the oracle's formula on the very same (bf16) snapshots: equal up to summation order
+        var_gpu_inputs.append(O.second_difference_variance([to_host_f64(s) for s in snaps_d[l]]))
+        # and on the oracle's own float64 caches: equal up to the bf16 storage of the features
+        var_orc.append(O.second_difference_variance(snaps_o[l]))
+    np.testing.assert_allclose(var_gpu, var_gpu_inputs, rtol=1e-9)
+    np.testing.assert_allclose(var_gpu, var_orc, rtol=0.05)
+    np.testing.assert_allclose(B.hero_stability_scores(var_gpu), O.stability_scores(var_orc), atol=0.05)
+    cache.close()

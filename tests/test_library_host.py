@@ -121,6 +121,20 @@ def test_null_and_small_buffers_are_rejected_before_any_gpu_work(lib):
     assert lib.hero_gather_ln(p, 7, None, None, 1, 64, p, p, 1e-5, p, None) == B.HERO_ERR_INVALID_ARG
 
 
+def test_stability_scores_host_function_matches_oracle(lib):
+    v = [4.0, 1.0, 2.5, 1.0, 3.25]
+    np.testing.assert_allclose(B.hero_stability_scores(v), O.stability_scores(v), rtol=0, atol=1e-15)
+    np.testing.assert_allclose(B.hero_stability_scores([2.0, 2.0]), [1.0, 1.0])
+    out = (ctypes.c_double * 2)()
+    bad = (ctypes.c_double * 2)(1.0, -1.0)
+    assert lib.hero_stability_scores(bad, 2, out) == B.HERO_ERR_INVALID_ARG
+    assert lib.hero_stability_scores(None, 2, out) == B.HERO_ERR_INVALID_ARG
+    p = ctypes.c_void_p(256)
+    assert lib.hero_second_diff_stats(p, p, p, 12, p, 1 << 20, p, 0, None) == B.HERO_ERR_SHAPE
+    assert lib.hero_second_diff_stats(p, p, p, 16, p, 64, p, 0, None) == B.HERO_ERR_BUFFER_TOO_SMALL
+    assert lib.hero_second_diff_stats(p, p, None, 16, p, 1 << 20, p, 0, None) == B.HERO_ERR_INVALID_ARG
+
+
 def test_product_path_does_not_import_the_oracle():
     pkg = os.path.join(ROOT, "paper_2508_17588_amd")
     for dirpath, _, files in os.walk(pkg):
