@@ -240,6 +240,116 @@ def select(ages: np.ndarray, cfg, step: int) -> Tuple[np.ndarray, np.ndarray]:
 # layer operations on a cache (Alg. 1)
 # ----------------------------------------------------------------------------
 
+# ----------------------------------------------------------------------------
+# the modulated block: the internals Sec. 3.2 leaves out "for clarity" (scale and
+# shift), as CogVideoX-style DiT blocks have them.  The paper fixes none of this;
+# each piece is the textbook definition and is pinned as such by the tests.
+# ----------------------------------------------------------------------------
+
+BLOCK_ADALN, BLOCK_QKNORM, BLOCK_ROPE = 1, 2, 4
+QK_NORM_EPS = 1e-6
+ROPE_THETA = 10000.0
+MOD_ROWS = ("shift1_v", "scale1_v", "gate1_v", "shift1_t", "scale1_t", "gate1_t",
+            "shift2_v", "scale2_v", "gate2_v", "shift2_t", "scale2_t", "gate2_t")
+
+
+def stream_vector(mod: np.ndarray, name: str, rows: np.ndarray, n_text: int) -> np.ndarray:
+    """Per-row modulation vector: row `name`_t of the table for text rows
+    (joint index < n_text), `name`_v for video rows.  -> [len(rows), d]."""
+    v = mod[MOD_ROWS.index(name + "_v")]
+    t = mod[MOD_ROWS.index(name + "_t")]
+    return np.where((np.asarray(rows) < n_text)[:, None], t[None, :], v[None, :])
+
+
+def head_layer_norm(x: np.ndarray, gain: np.ndarray, bias: np.ndarray, n_heads: int) -> np.ndarray:
+    """LayerNorm over each head's channels separately (q/k normalisation), eps 1e-6,
+    one gain/bias vector [head_dim] shared by all heads."""
+    r, d = x.shape
+    xh = x.reshape(r, n_heads, d // n_heads)
+    return layer_norm(xh, gain, bias, QK_NORM_EPS).reshape(r, d)
+
+
+def rope_angles(frames: int, height: int, width: int, head_dim: int) -> np.ndarray:
+    """Rotation angles of the 3-D rotary position embedding, [frames*height*width, head_dim/2].
+
+    The head's channel pairs are split between the axes: head_dim/8 pairs for t,
+    then 3*head_dim/16 pairs each for y and x (16 / 24 / 24 channels at head_dim
+    64).  Pair i of an axis with n pairs turns by pos * theta^(-i/n), theta = 10000.
+    Token order (t, y, x) row-major, as in the joint sequence."""
+    n_t, n_y = head_dim // 8, (head_dim // 16) * 3
+    n_x = head_dim // 2 - n_t - n_y
+    t, y, x = np.meshgrid(np.arange(frames), np.arange(height), np.arange(width), indexing="ij")
+    parts = []
+    for pos, n in ((t, n_t), (y, n_y), (x, n_x)):
+        freq = ROPE_THETA ** (-np.arange(n, dtype=np.float64) / n)
+        parts.append(pos.reshape(-1, 1).astype(np.float64) * freq[None, :])
+    return np.concatenate(parts, axis=1)
+
+
+def apply_rope(x: np.ndarray, angles: np.ndarray, n_heads: int) -> np.ndarray:
+    """Rotate the channel pairs (2i, 2i+1) of every head by angles[:, i]:
+    (a, b) -> (a cos - b sin, a sin + b cos).  angles: [rows, head_dim/2]."""
+    r, d = x.shape
+    xh = x.reshape(r, n_heads, d // n_heads // 2, 2)
+    c, s_ = np.cos(angles)[:, None, :], np.sin(angles)[:, None, :]
+    a, b = xh[..., 0], xh[..., 1]
+    return np.stack([a * c - b * s_, a * s_ + b * c], axis=-1).reshape(r, d)
+
+
+class BlockExt:
+    """What the modulated block needs beyond the plain one: which parts are on, the
+    number of text rows (they take the text-stream modulation and no rotation) and
+    the rotation angles of the video tokens."""
+
+    def __init__(self, cfg):
+        self.flags = int(getattr(cfg, "block_flags", 0))
+        self.n_text = cfg.n_text
+        self.n_heads = cfg.n_heads
+        self.angles = (rope_angles(cfg.frames, cfg.height, cfg.width, cfg.head_dim)
+                       if self.flags & BLOCK_ROPE else None)
+
+    def ln(self, x_rows, rows, w, which, eps):
+        u = layer_norm(x_rows, w[f"ln{which}_g"], w[f"ln{which}_b"], eps)
+        if self.flags & BLOCK_ADALN:
+            u = (u * (1.0 + stream_vector(w["mod"], f"scale{which}", rows, self.n_text))
+                 + stream_vector(w["mod"], f"shift{which}", rows, self.n_text))
+        return u
+
+    def gate(self, g_rows, rows, w, which):
+        if self.flags & BLOCK_ADALN:
+            return g_rows * stream_vector(w["mod"], f"gate{which}", rows, self.n_text)
+        return g_rows
+
+    def qk(self, q, k, rows, w):
+        if self.flags & BLOCK_QKNORM:
+            q = head_layer_norm(q, w["qn_g"], w["qn_b"], self.n_heads)
+            k = head_layer_norm(k, w["kn_g"], w["kn_b"], self.n_heads)
+        if self.flags & BLOCK_ROPE:
+            rows = np.asarray(rows)
+            vid = rows >= self.n_text
+            if vid.any():
+                ang = self.angles[rows[vid] - self.n_text]
+                q, k = q.copy(), k.copy()
+                q[vid] = apply_rope(q[vid], ang, self.n_heads)
+                k[vid] = apply_rope(k[vid], ang, self.n_heads)
+        return q, k
+
+
+def refresh_rows_ext(x: np.ndarray, w, cache: "LayerCache", idx: np.ndarray, ext: BlockExt, eps: float) -> None:
+    """Eq. 3 on rows idx with the modulated block; updates the cache in place.
+    Cached features are what is added to the stream, i.e. after the gate."""
+    d = x.shape[1]
+    u = ext.ln(x[idx], idx, w, 1, eps)
+    qkv = linear(u, w["w_qkv"], w["b_qkv"])
+    q, k = ext.qk(qkv[:, :d], qkv[:, d:2 * d], idx, w)
+    cache.k[idx] = k
+    cache.v[idx] = qkv[:, 2 * d:]
+    g_attn = ext.gate(linear(attention(q, cache.k, cache.v, ext.n_heads), w["w_o"], w["b_o"]), idx, w, 1)
+    cache.g_attn[idx] = g_attn
+    a = x[idx] + g_attn
+    cache.g_ffn[idx] = ext.gate(ffn(ext.ln(a, idx, w, 2, eps), w), idx, w, 2)
+
+
 class LayerCache:
     """Cached features of one layer: G of the attention branch and of the FFN
     branch for all N rows (the paper's G on video rows, H on text rows), the
@@ -335,14 +445,37 @@ class HeroOracle:
     def is_full_step(self, step: int) -> bool:
         return step % self.cfg.interval == 0
 
+    def _ext(self):
+        if not hasattr(self, "_ext_cached"):
+            self._ext_cached = BlockExt(self.cfg) if getattr(self.cfg, "block_flags", 0) else None
+        return self._ext_cached
+
     def full_layer(self, layer: int, x: np.ndarray) -> np.ndarray:
         c = self.cfg
         shallow = layer < c.n_shallow
+        if self._ext() is not None:
+            # the modulated block on all rows: a refresh of every row into a fresh cache
+            x = np.asarray(x, self.dtype)
+            cache, n = self.caches[layer], x.shape[0]
+            if not shallow:
+                cache.g_attn_prev, cache.g_ffn_prev = cache.g_attn, cache.g_ffn
+            cache.g_attn, cache.g_ffn = np.zeros_like(x), np.zeros_like(x)
+            cache.k, cache.v = np.zeros_like(x), np.zeros_like(x)
+            refresh_rows_ext(x, self.w[layer], cache, np.arange(n), self._ext(), c.ln_eps)
+            cache.n_fills += 1
+            return x + cache.g_attn + cache.g_ffn
         return full_layer(np.asarray(x, self.dtype), self.w[layer], self.caches[layer],
                           c.n_heads, c.ln_eps, keep_kv=shallow, keep_prev=not shallow)
 
     def refresh_layer(self, layer: int, x: np.ndarray, idx: np.ndarray) -> np.ndarray:
         c = self.cfg
+        if self._ext() is not None:
+            x = np.asarray(x, self.dtype)
+            idx = np.asarray(idx, dtype=np.int64)
+            cache = self.caches[layer]
+            if len(idx):
+                refresh_rows_ext(x, self.w[layer], cache, idx, self._ext(), c.ln_eps)
+            return x + cache.g_attn + cache.g_ffn
         return refresh_layer(np.asarray(x, self.dtype), self.w[layer], self.caches[layer],
                              idx, c.n_heads, c.ln_eps)
 

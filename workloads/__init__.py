@@ -20,7 +20,7 @@ import numpy as np
 __all__ = [
     "HeroConfig", "CONFIGS", "get_config", "round_to_bf16", "bf16_bits",
     "from_bf16_bits", "make_layer_weights", "make_tokens", "perturb_tokens",
-    "euler_update", "WEIGHT_NAMES",
+    "euler_update", "WEIGHT_NAMES", "make_block_extras", "MOD_ROWS", "BLOCK_ADALN", "BLOCK_QKNORM", "BLOCK_ROPE",
 ]
 
 
@@ -53,6 +53,7 @@ class HeroConfig:
     seed: int = 1234          # selection seed
     resid_fp32: bool = True   # residual stream x kept in fp32 on the GPU
     select_mode: int = 0      # 0: age-priority selection, 1: age-weighted random sampling (Sec. 3.3)
+    block_flags: int = 0      # bit 0: adaLN shift/scale/gate, bit 1: per-head q/k LayerNorm, bit 2: 3-D rotary positions
 
     @property
     def n_video(self) -> int:
@@ -182,6 +183,33 @@ def make_layer_weights(cfg: HeroConfig, layer: int, seed: int = 0,
         w[nm + "_g"] = round_to_bf16(g)
         w[nm + "_b"] = round_to_bf16(b)
     return w
+
+
+BLOCK_ADALN, BLOCK_QKNORM, BLOCK_ROPE = 1, 2, 4
+MOD_ROWS = ("shift1_v", "scale1_v", "gate1_v", "shift1_t", "scale1_t", "gate1_t",
+            "shift2_v", "scale2_v", "gate2_v", "shift2_t", "scale2_t", "gate2_t")
+
+
+def make_block_extras(cfg: HeroConfig, layer: int, seed: int = 0, step: int = 0, noise: float = 0.1
+                      ) -> Dict[str, np.ndarray]:
+    """Seeded draws of the extra parameters of the modulated block: per-head q/k
+    LayerNorm gain/bias ([head_dim], 1/0 plus noise) and the modulation table
+    "mod" [12, hidden] (rows as in MOD_ROWS; shift, scale ~ N(0, noise), gate ~
+    1 + N(0, noise)), which depends on `step` the way a timestep embedding would.
+    All values are bf16-representable.  Pure draws: no method arithmetic."""
+    rng = np.random.default_rng([seed, layer, 0xADA])
+    hd, d = cfg.head_dim, cfg.hidden
+    out = {}
+    for nm in ("qn", "kn"):
+        out[nm + "_g"] = round_to_bf16(1 + rng.standard_normal(hd, dtype=np.float32) * np.float32(noise))
+        out[nm + "_b"] = round_to_bf16(rng.standard_normal(hd, dtype=np.float32) * np.float32(noise))
+    rs = np.random.default_rng([seed, layer, step, 0x30D])
+    mod = rs.standard_normal((12, d), dtype=np.float32) * np.float32(noise)
+    for i, nm in enumerate(MOD_ROWS):
+        if nm.startswith("gate"):
+            mod[i] += 1.0
+    out["mod"] = round_to_bf16(mod)
+    return out
 
 
 def make_tokens(cfg: HeroConfig, seed: int = 1) -> np.ndarray:
