@@ -52,6 +52,18 @@ enum { HERO_DTYPE_BF16 = 0, HERO_DTYPE_FP32 = 1 };
  * AGE_WEIGHTED: n_p draws without replacement, probability proportional to min(age, 65535) + 1 among
  * the tokens still left (row-major order inside the patch), listed in draw order. */
 enum { HERO_SELECT_AGE_PRIORITY = 0, HERO_SELECT_AGE_WEIGHTED = 1 };
+/* Block internals that Sec. 3.2 leaves out "for clarity", as CogVideoX-style DiT blocks have them
+ * (rows < n_text are the text stream, all others the video stream):
+ * ADALN:  u = LN(x) * (1 + scale_s) + shift_s before each branch and G = gate_s * F(u) after it,
+ *         with per-stream vectors from the layer's modulation table (hero_layer_weights.mod);
+ *         the cached features are the gated ones (what is added to the stream).
+ * QKNORM: LayerNorm (eps 1e-6, gain/bias of head_dim elements shared by the heads) over each
+ *         head's channels of q and of k.
+ * ROPE:   3-D rotary positions on q and k of video rows: of a head's head_dim/2 channel pairs
+ *         (2i, 2i+1) the first head_dim/8 turn with t, the next 3*head_dim/16 with y, the rest
+ *         with x; pair i of an axis with n pairs turns by pos * 10000^(-i/n).  Text rows and V are
+ *         not rotated.  Order: projection, QKNORM, ROPE, softmax scale. */
+enum { HERO_BLOCK_ADALN = 1, HERO_BLOCK_QKNORM = 2, HERO_BLOCK_ROPE = 4 };
 
 /* Plain-data configuration, copied at hero_cache_create(). */
 typedef struct hero_config {
@@ -70,7 +82,7 @@ typedef struct hero_config {
   float   ln_eps;
   uint64_t seed;       /* selection seed                                                 */
   int32_t select_mode; /* HERO_SELECT_AGE_PRIORITY or HERO_SELECT_AGE_WEIGHTED (Sec. 3.3 tracking) */
-  int32_t reserved;    /* must be 0                                                      */
+  int32_t block_flags; /* 0: the plain block of Eq. 2; or a sum of HERO_BLOCK_* (see below)        */
 } hero_config;
 
 /* Borrowed device pointers to one block's parameters (bf16). */
@@ -81,6 +93,12 @@ typedef struct hero_layer_weights {
   const void *ln2_g, *ln2_b;   /* [hidden]                */
   const void *w_ff1, *b_ff1;   /* [ffn_dim, hidden], [ffn_dim] */
   const void *w_ff2, *b_ff2;   /* [hidden, ffn_dim], [hidden]  */
+  /* used only with the matching HERO_BLOCK_* flag (may be NULL otherwise) */
+  const void *q_norm_g, *q_norm_b, *k_norm_g, *k_norm_b;   /* [head_dim] each (QKNORM) */
+  const void *mod;             /* [12, hidden] bf16 (ADALN), rows: shift, scale, gate of the attention branch for
+                                  the video stream, the same three for the text stream, then the six of the FFN
+                                  branch in the same order.  Borrowed: the caller may rewrite its contents between
+                                  calls (a new timestep), in stream order. */
 } hero_layer_weights;
 
 typedef struct hero_cache* hero_cache_t;   /* opaque host-side handle owned by the library */
@@ -170,7 +188,7 @@ int hero_cache_state(hero_cache_t c, int32_t* n_full, int32_t* last_full_step);
 enum {
   HERO_PROF_SELECT = 0, HERO_PROF_LN = 1, HERO_PROF_GEMM_QKV = 2, HERO_PROF_ATTN = 3,
   HERO_PROF_GEMM_O = 4, HERO_PROF_GEMM_FF1 = 5, HERO_PROF_GEMM_FF2 = 6, HERO_PROF_RESID = 7,
-  HERO_PROF_EXTRAP = 8, HERO_PROF_DEEPSUM = 9, HERO_PROF_KINDS = 10
+  HERO_PROF_EXTRAP = 8, HERO_PROF_DEEPSUM = 9, HERO_PROF_QKPOST = 10, HERO_PROF_KINDS = 11
 };
 int hero_profile_begin(hero_cache_t c);
 /* The same, bracketing only the kinds whose bit (1u << kind) is set in kind_mask: each bracket

@@ -27,10 +27,12 @@ DTYPE_FP32 = 1
 
 VIEW_S_CUR, VIEW_S_PREV, VIEW_K, VIEW_VT, VIEW_AGES, VIEW_IDX = range(6)
 
-PROF_KINDS = ("select", "ln", "gemm_qkv", "attention", "gemm_o", "gemm_ff1", "gemm_ff2", "resid", "extrap", "deepsum")
+PROF_KINDS = ("select", "ln", "gemm_qkv", "attention", "gemm_o", "gemm_ff1", "gemm_ff2", "resid", "extrap", "deepsum", "qk_post")
 
 WEIGHT_FIELDS = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
                  "ln2_g", "ln2_b", "w_ff1", "b_ff1", "w_ff2", "b_ff2")
+EXTRA_WEIGHT_FIELDS = ("q_norm_g", "q_norm_b", "k_norm_g", "k_norm_b", "mod")
+BLOCK_ADALN, BLOCK_QKNORM, BLOCK_ROPE = 1, 2, 4
 
 EXPORTS = (
     "hero_last_error", "hero_num_selected", "hero_cache_bytes", "hero_cache_create",
@@ -54,11 +56,11 @@ class hero_config(Structure):
                 ("frames", c_int32), ("height", c_int32), ("width", c_int32), ("n_text", c_int32),
                 ("patch_h", c_int32), ("patch_w", c_int32), ("ratio", c_float),
                 ("resid_dtype", c_int32), ("ln_eps", c_float), ("seed", c_uint64),
-                ("select_mode", c_int32), ("reserved", c_int32)]
+                ("select_mode", c_int32), ("block_flags", c_int32)]
 
 
 class hero_layer_weights(Structure):
-    _fields_ = [(n, c_void_p) for n in WEIGHT_FIELDS]
+    _fields_ = [(n, c_void_p) for n in WEIGHT_FIELDS + EXTRA_WEIGHT_FIELDS]
 
 
 _lib = None
@@ -122,7 +124,7 @@ def make_config(cfg, resid_fp32: Optional[bool] = None) -> hero_config:
     return hero_config(cfg.n_layers, cfg.n_shallow, cfg.interval, cfg.hidden, cfg.n_heads, cfg.head_dim,
                        cfg.ffn_dim, cfg.frames, cfg.height, cfg.width, cfg.n_text, cfg.patch_h, cfg.patch_w,
                        cfg.ratio, DTYPE_FP32 if rf else DTYPE_BF16, cfg.ln_eps, cfg.seed,
-                       getattr(cfg, "select_mode", 0), 0)
+                       getattr(cfg, "select_mode", 0), getattr(cfg, "block_flags", 0))
 
 
 def _stream() -> c_void_p:
@@ -204,6 +206,10 @@ class HeroCache:
         for n in WEIGHT_FIELDS:
             _need(w[n], torch.bfloat16, n)
             setattr(st, n, w[n].data_ptr())
+        for n in EXTRA_WEIGHT_FIELDS:          # only needed with the matching block flag
+            if w.get(n) is not None:
+                _need(w[n], torch.bfloat16, n)
+                setattr(st, n, w[n].data_ptr())
         self._weights.append(w)
         _check(self.lib.hero_set_layer_weights(self.handle, layer, byref(st)))
 

@@ -262,6 +262,15 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_kernel(GemmAr
   }
   const float out_scale = (EPI == EPI_QKV && n0 + wn0 < g.d) ? g.q_scale : 1.0f;
   const int ncol = n0 + wn0 + lr - n_shift;
+  // adaLN gate of the lane's columns, for the video and the text stream
+  const bool gated = (EPI == EPI_SCATTER || EPI == EPI_SCATTER_ADD) && g.gate_v != nullptr;
+  float gate_v[NB], gate_t[NB];
+#pragma unroll
+  for (int j = 0; j < NB; ++j) {
+    const int n = n0 + wn0 + j * 32 + lr;
+    gate_v[j] = (gated && n_ok[j]) ? bf16_to_f32(g.gate_v[n]) : 1.f;
+    gate_t[j] = (gated && n_ok[j]) ? bf16_to_f32(g.gate_t[n]) : 1.f;
+  }
 #pragma unroll
   for (int i = 0; i < MB; ++i) {
 #pragma unroll
@@ -276,6 +285,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_kernel(GemmAr
           for (int j = 0; j < NB; ++j) {
             if (n_ok[j]) {
               float v = acc[i][j][4 * q + e] + bias[j];
+              if (gated) v *= row < g.n_text ? gate_t[j] : gate_v[j];
               if (EPI == EPI_QKV) v *= out_scale;
               if (EPI == EPI_GELU) v = gelu_tanh(v);
               if (EPI == EPI_SCATTER_ADD) v += bf16_to_f32(prow[j * 32]);
@@ -646,11 +656,36 @@ __device__ __forceinline__ void epilogue256(const GemmArgs& g, floatx16_t (&acc)
       const int n = min(nw + 32 * j + 8 * q + 4 * lh, g.n - 4);     // columns past N are never stored
       bias4[j][q] = *reinterpret_cast<const u32x2_t*>(g.bias + n);
     }
+  // adaLN gate of the lane's columns, for both streams; the lane's row i picks one
+  constexpr bool CAN_GATE = EPI == EPI_SCATTER || EPI == EPI_SCATTER_ADD;
+  const bool gated = CAN_GATE && g.gate_v != nullptr;
+  u32x2_t gate4_v[2][4], gate4_t[2][4];
+  bool text_row[4] = {false, false, false, false};
+  if (gated) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int n = min(nw + 32 * j + 8 * q + 4 * lh, g.n - 4);
+        gate4_v[j][q] = *reinterpret_cast<const u32x2_t*>(g.gate_v + n);
+        gate4_t[j][q] = *reinterpret_cast<const u32x2_t*>(g.gate_t + n);
+      }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int m = min(mw + 32 * i + lr, g.m - 1);
+      text_row[i] = (use_rows ? g.rows[m] : m) < g.n_text;
+    }
+  }
   auto biased = [&](int i, int j, int q, float* v) {
     v[0] = acc[i][j][4 * q] + unpack_lo(bias4[j][q][0]);
     v[1] = acc[i][j][4 * q + 1] + unpack_hi(bias4[j][q][0]);
     v[2] = acc[i][j][4 * q + 2] + unpack_lo(bias4[j][q][1]);
     v[3] = acc[i][j][4 * q + 3] + unpack_hi(bias4[j][q][1]);
+    if (gated) {
+      const u32x2_t gg = text_row[i] ? gate4_t[j][q] : gate4_v[j][q];
+      v[0] *= unpack_lo(gg[0]); v[1] *= unpack_hi(gg[0]);
+      v[2] *= unpack_lo(gg[1]); v[3] *= unpack_hi(gg[1]);
+    }
   };
 
   if (EPI == EPI_SCATTER_ADD) {

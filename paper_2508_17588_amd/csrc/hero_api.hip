@@ -64,7 +64,10 @@ int check_config(const hero_config* c) {
     return fail(HERO_ERR_INVALID_ARG, "select_mode must be HERO_SELECT_AGE_PRIORITY or HERO_SELECT_AGE_WEIGHTED");
   if (c->select_mode == HERO_SELECT_AGE_WEIGHTED && (int64_t)c->patch_h * c->patch_w > 65535)
     return fail(HERO_ERR_SHAPE, "age-weighted selection needs patches of at most 65535 tokens");
-  if (c->reserved != 0) return fail(HERO_ERR_INVALID_ARG, "reserved must be 0");
+  if (c->block_flags < 0 || c->block_flags > (HERO_BLOCK_ADALN | HERO_BLOCK_QKNORM | HERO_BLOCK_ROPE))
+    return fail(HERO_ERR_INVALID_ARG, "block_flags must be a sum of HERO_BLOCK_* values");
+  if ((c->block_flags & HERO_BLOCK_ROPE) && c->head_dim % 16 != 0)
+    return fail(HERO_ERR_SHAPE, "rotary positions need head_dim to be a multiple of 16");
   if (c->head_dim != 32 && c->head_dim != 64) return fail(HERO_ERR_SHAPE, "head_dim must be 32 or 64");
   if (c->hidden != c->n_heads * c->head_dim || c->n_heads < 1)
     return fail(HERO_ERR_SHAPE, "hidden must equal n_heads * head_dim");
@@ -102,6 +105,7 @@ struct Layout {
   size_t layer_stride_shallow, layer_stride_deep;
   size_t s_bytes, k_bytes, vt_bytes;
   size_t t_off[2], t_bytes;      // fp32 sums of the deep layers' features (two generations); 0 bytes if < 2 deep layers
+  size_t rope_off, rope_bytes;   // (cos, sin) of every video token's rotation angles; 0 bytes without HERO_BLOCK_ROPE
   size_t cache_bytes;
   // workspace
   size_t idx_off, a_off, q_off, o_off, f_off, ktmp_off, vtmp_off, splitk_off, splitk_bytes, ws_bytes;
@@ -123,6 +127,8 @@ Layout make_layout(const hero_config& c) {
   L.t_bytes = (c.n_layers - c.n_shallow >= 2) ? align_up((size_t)L.n_tokens * c.hidden * 4, 256) : 0;
   L.t_off[0] = off; off += L.t_bytes;
   L.t_off[1] = off; off += L.t_bytes;
+  L.rope_bytes = (c.block_flags & HERO_BLOCK_ROPE) ? align_up((size_t)L.n_video * (c.head_dim / 2) * sizeof(float2), 256) : 0;
+  L.rope_off = off; off += L.rope_bytes;
   L.cache_bytes = off;
   size_t w = 0;
   L.idx_off = w; w += align_up((size_t)L.n_tokens * 4, 256);
@@ -187,6 +193,7 @@ struct hero_cache {
   int32_t* idx = nullptr;
   bf16_t *a = nullptr, *q = nullptr, *o = nullptr, *f = nullptr, *ktmp = nullptr, *vtmp = nullptr;
   float* splitk = nullptr;        // GEMM k-split partial sums (nullptr when the problem is too small to need them)
+  float2* rope = nullptr;         // rotation table (nullptr without HERO_BLOCK_ROPE)
   std::vector<LayerState> layers;
   // deep-stack sums: slot i holds sum_l S_cur^l taken when the deep layers' fill counts were
   // t_key[i] (t_is_prev[i] false), or the matching previous-generation sum (t_is_prev[i] true)
@@ -242,18 +249,43 @@ int run_block_rows(hero_cache_t c, LayerState& ls, void* x, const int32_t* rows,
   const double xsz = x_fp32 ? 4.0 : 2.0;
   const double rd = (double)n_rows * d;
   const double n_all = (double)c->lay.n_tokens;
+  // modulated block: rows of the modulation table (d elements each): shift, scale, gate of the
+  // attention branch for the video stream, then for the text stream, then the same six for the FFN
+  const bool adaln = (cfg.block_flags & HERO_BLOCK_ADALN) != 0;
+  const bool qk_post = (cfg.block_flags & (HERO_BLOCK_QKNORM | HERO_BLOCK_ROPE)) != 0;
+  const bf16_t* mod = (const bf16_t*)w.mod;
+  LnMod m1, m2;
+  if (adaln) {
+    m1.shift_v = mod + 0 * d; m1.scale_v = mod + 1 * d; m1.shift_t = mod + 3 * d; m1.scale_t = mod + 4 * d;
+    m2.shift_v = mod + 6 * d; m2.scale_v = mod + 7 * d; m2.shift_t = mod + 9 * d; m2.scale_t = mod + 10 * d;
+    m1.n_text = m2.n_text = cfg.n_text;
+  }
   PROF_LAUNCH(c, HERO_PROF_LN, rd * (xsz + 2.0), st,
               launch_gather_ln(x, x_fp32, nullptr, rows, n_rows, d, (const bf16_t*)w.ln1_g,
-                               (const bf16_t*)w.ln1_b, cfg.ln_eps, c->a, st));
+                               (const bf16_t*)w.ln1_b, cfg.ln_eps, c->a, st, m1));
   GemmArgs g;
   memset(&g, 0, sizeof(g));
   g.a = c->a; g.w = (const bf16_t*)w.w_qkv; g.bias = (const bf16_t*)w.b_qkv;
   g.m = n_rows; g.n = 3 * d; g.k = d; g.epilogue = EPI_QKV; g.rows = rows;
   g.c = c->q; g.k_out = k_dst; g.vt_out = vt_dst; g.ld_vt = c->lay.n_pad; g.d = d;
   // softmax scale and the change to base 2 are folded into Q before its single bf16 rounding
-  g.q_scale = 1.4426950408889634f / sqrtf((float)cfg.head_dim);
+  // (with q/k post-processing the scale is applied there, after the normalisation and rotation)
+  const float softmax_scale = 1.4426950408889634f / sqrtf((float)cfg.head_dim);
+  g.q_scale = qk_post ? 1.0f : softmax_scale;
   g.splitk_ws = c->splitk; g.splitk_ws_bytes = c->lay.splitk_bytes;
   PROF_LAUNCH(c, HERO_PROF_GEMM_QKV, 6.0 * rd * d, st, launch_gemm(g, st));
+  if (qk_post) {
+    QkPostArgs qa;
+    memset(&qa, 0, sizeof(qa));
+    qa.q = c->q; qa.k = k_dst; qa.rows = rows; qa.n_rows = n_rows; qa.d = d; qa.head_dim = cfg.head_dim;
+    qa.n_text = cfg.n_text; qa.q_scale = softmax_scale;
+    if (cfg.block_flags & HERO_BLOCK_QKNORM) {
+      qa.qn_g = (const bf16_t*)w.q_norm_g; qa.qn_b = (const bf16_t*)w.q_norm_b;
+      qa.kn_g = (const bf16_t*)w.k_norm_g; qa.kn_b = (const bf16_t*)w.k_norm_b;
+    }
+    if (cfg.block_flags & HERO_BLOCK_ROPE) qa.rope = c->rope;
+    PROF_LAUNCH(c, HERO_PROF_QKPOST, rd * 8.0, st, launch_qk_post(qa, st));      // q and k rows, in and out
+  }
 
   AttnArgs at;
   at.q = c->q; at.k = k_dst; at.vt = vt_dst; at.ld_vt = c->lay.n_pad; at.o = c->o;
@@ -264,12 +296,13 @@ int run_block_rows(hero_cache_t c, LayerState& ls, void* x, const int32_t* rows,
   memset(&g, 0, sizeof(g));
   g.a = c->o; g.w = (const bf16_t*)w.w_o; g.bias = (const bf16_t*)w.b_o;
   g.m = n_rows; g.n = d; g.k = d; g.epilogue = EPI_SCATTER; g.rows = rows; g.c = s_dst;
+  if (adaln) { g.gate_v = mod + 2 * d; g.gate_t = mod + 5 * d; g.n_text = cfg.n_text; }
   g.splitk_ws = c->splitk; g.splitk_ws_bytes = c->lay.splitk_bytes;
   PROF_LAUNCH(c, HERO_PROF_GEMM_O, 2.0 * rd * d, st, launch_gemm(g, st));
 
   PROF_LAUNCH(c, HERO_PROF_LN, rd * (xsz + 4.0), st,
               launch_gather_ln(x, x_fp32, s_dst, rows, n_rows, d, (const bf16_t*)w.ln2_g,
-                               (const bf16_t*)w.ln2_b, cfg.ln_eps, c->a, st));
+                               (const bf16_t*)w.ln2_b, cfg.ln_eps, c->a, st, m2));
   memset(&g, 0, sizeof(g));
   g.a = c->a; g.w = (const bf16_t*)w.w_ff1; g.bias = (const bf16_t*)w.b_ff1;
   g.m = n_rows; g.n = cfg.ffn_dim; g.k = d; g.epilogue = EPI_GELU; g.c = c->f;
@@ -279,6 +312,7 @@ int run_block_rows(hero_cache_t c, LayerState& ls, void* x, const int32_t* rows,
   memset(&g, 0, sizeof(g));
   g.a = c->f; g.w = (const bf16_t*)w.w_ff2; g.bias = (const bf16_t*)w.b_ff2;
   g.m = n_rows; g.n = d; g.k = cfg.ffn_dim; g.epilogue = EPI_SCATTER_ADD; g.rows = rows; g.c = s_dst;
+  if (adaln) { g.gate_v = mod + 8 * d; g.gate_t = mod + 11 * d; g.n_text = cfg.n_text; }
   if (fuse_resid != nullptr) {
     *fuse_resid = gemm_can_update_x(g);
     if (*fuse_resid) { g.x = x; g.x_fp32 = x_fp32 ? 1 : 0; }
@@ -404,6 +438,7 @@ int hero_cache_create(const hero_config* cfg, void* dev_cache, size_t cache_byte
   c->splitk = L.splitk_bytes ? (float*)(c->ws + L.splitk_off) : nullptr;
   c->layers.resize(cfg->n_layers);
   if (L.t_bytes) { c->t[0] = (float*)(c->cache + L.t_off[0]); c->t[1] = (float*)(c->cache + L.t_off[1]); }
+  if (L.rope_bytes) c->rope = (float2*)(c->cache + L.rope_off);
   size_t off = align_up((size_t)L.n_video * 4, 256);
   for (int l = 0; l < cfg->n_layers; ++l) {
     LayerState& ls = c->layers[l];
@@ -420,9 +455,11 @@ int hero_cache_create(const hero_config* cfg, void* dev_cache, size_t cache_byte
   hipStream_t st = (hipStream_t)stream;
   hipError_t e = hipMemsetAsync(dev_cache, 0, L.cache_bytes, st);
   if (e == hipSuccess) e = hipMemsetAsync(dev_workspace, 0, L.ws_bytes, st);
+  if (e == hipSuccess && c->rope)
+    e = launch_rope_table(c->rope, cfg->frames, cfg->height, cfg->width, cfg->head_dim, st);
   if (e != hipSuccess) {
     delete c;
-    return fail(HERO_ERR_HIP, "hipMemsetAsync: %s", hipGetErrorString(e));
+    return fail(HERO_ERR_HIP, "cache set-up: %s", hipGetErrorString(e));
   }
   *out = c;
   return HERO_OK;
@@ -456,7 +493,10 @@ int hero_set_layer_weights(hero_cache_t c, int32_t layer, const hero_layer_weigh
   if (rc) return rc;
   if (!w) return fail(HERO_ERR_INVALID_ARG, "weights pointer is null");
   const void* const* p = reinterpret_cast<const void* const*>(w);
+  const int flags = c->cfg.block_flags;
   for (size_t i = 0; i < sizeof(*w) / sizeof(void*); ++i) {
+    const bool needed = i < 12 || (i < 16 ? (flags & HERO_BLOCK_QKNORM) != 0 : (flags & HERO_BLOCK_ADALN) != 0);
+    if (!needed) continue;
     if (!p[i]) return fail(HERO_ERR_INVALID_ARG, "weight pointer %zu of layer %d is null", i, layer);
     if ((uintptr_t)p[i] & 15) return fail(HERO_ERR_INVALID_ARG, "weight pointer %zu of layer %d is not 16-byte aligned", i, layer);
   }

@@ -22,9 +22,28 @@ hipError_t launch_fill_i32(int32_t* p, int32_t v, int64_t n, hipStream_t st);
 // mode 0: age priority (largest (age, hash) keys); mode 1: age-weighted sampling without replacement
 hipError_t launch_select(const SelectGeom& g, int mode, uint32_t step_salt, int32_t* ages, int32_t* idx,
                          hipStream_t st);
+// adaLN modulation of a LayerNorm's output, u * (1 + scale) + shift, with the vectors of the row's
+// stream (rows < n_text: text).  scale_v == nullptr: none.
+struct LnMod {
+  const bf16_t *scale_v = nullptr, *shift_v = nullptr, *scale_t = nullptr, *shift_t = nullptr;
+  int32_t n_text = 0;
+};
 hipError_t launch_gather_ln(const void* x, bool x_fp32, const bf16_t* add, const int32_t* rows, int n_rows,
                             int hidden, const bf16_t* gain, const bf16_t* bias, float eps, bf16_t* out,
-                            hipStream_t st);
+                            hipStream_t st, const LnMod& mod = LnMod());
+
+// q / k post-processing (per-head LayerNorm, rotary positions on video rows, softmax scale on q), in place
+struct QkPostArgs {
+  bf16_t* q;                 // [n_rows, d]
+  bf16_t* k;                 // [*, d], row rows[i] (or i)
+  const int32_t* rows;
+  int32_t n_rows, d, head_dim, n_text;
+  const bf16_t *qn_g, *qn_b, *kn_g, *kn_b;   // [head_dim]; qn_g == nullptr: no normalisation
+  const float2* rope;        // [n_video, head_dim/2] (cos, sin); nullptr: no rotation
+  float q_scale;
+};
+hipError_t launch_qk_post(const QkPostArgs& a, hipStream_t st);
+hipError_t launch_rope_table(float2* table, int frames, int height, int width, int head_dim, hipStream_t st);
 hipError_t launch_axpy_features(void* x, bool x_fp32, const bf16_t* s_cur, const bf16_t* s_prev, float alpha,
                                 int64_t n_elems, hipStream_t st);
 
@@ -69,6 +88,9 @@ struct GemmArgs {
   size_t splitk_ws_bytes;
   void* x;              // SCATTER_ADD, optional: x[row(m), :] += the stored (rounded) S[row(m), :]  (Alg. 1 residual add)
   int32_t x_fp32;       // x holds fp32 (else bf16)
+  const bf16_t* gate_v; // SCATTER*, optional: (acc + bias) is multiplied by gate[n] of the row's stream (adaLN gate)
+  const bf16_t* gate_t; //   rows (after row(m)) below n_text use gate_t, the others gate_v
+  int32_t n_text;
 };
 
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t st);

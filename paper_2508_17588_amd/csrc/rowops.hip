@@ -143,11 +143,14 @@ template <typename XT, int ITERS>
 __global__ __launch_bounds__(256) void gather_ln_kernel(
     const XT* __restrict__ x, const bf16_t* __restrict__ add, const int32_t* __restrict__ rows,
     int n_rows, int hidden, const bf16_t* __restrict__ gain, const bf16_t* __restrict__ bias,
-    float eps, bf16_t* __restrict__ out) {
+    float eps, bf16_t* __restrict__ out, LnMod mod) {
   int lane = threadIdx.x & 63;
   int r = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (r >= n_rows) return;
   int64_t src = rows ? (int64_t)rows[r] : (int64_t)r;
+  // adaLN: the row's stream (text rows come first) picks the scale and shift vectors
+  const bf16_t* mscale = mod.scale_v ? (src < mod.n_text ? mod.scale_t : mod.scale_v) : nullptr;
+  const bf16_t* mshift = mod.scale_v ? (src < mod.n_text ? mod.shift_t : mod.shift_v) : nullptr;
   const XT* xr = x + src * hidden;
   const bf16_t* ar = add ? add + src * hidden : nullptr;
   int n_chunks = hidden >> 3;
@@ -192,6 +195,13 @@ __global__ __launch_bounds__(256) void gather_ln_kernel(
       ResidIO<bf16_t>::load8(bias + c * 8, b8);
 #pragma unroll
       for (int j = 0; j < 8; ++j) o8[j] = (v[it][j] - mean) * rstd * g8[j] + b8[j];
+      if (mscale) {
+        float sc8[8], sh8[8];
+        ResidIO<bf16_t>::load8(mscale + c * 8, sc8);
+        ResidIO<bf16_t>::load8(mshift + c * 8, sh8);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) o8[j] = o8[j] * (1.0f + sc8[j]) + sh8[j];
+      }
       ResidIO<bf16_t>::store8(orow + c * 8, o8);
     }
   }
@@ -200,13 +210,13 @@ __global__ __launch_bounds__(256) void gather_ln_kernel(
 template <typename XT>
 static hipError_t gather_ln_dispatch(const void* x, const bf16_t* add, const int32_t* rows, int n_rows,
                                      int hidden, const bf16_t* gain, const bf16_t* bias, float eps,
-                                     bf16_t* out, hipStream_t st) {
+                                     bf16_t* out, const LnMod& mod, hipStream_t st) {
   int iters = (hidden / 8 + 63) / 64;
   dim3 grid((n_rows + 3) / 4), block(256);
   const XT* xp = static_cast<const XT*>(x);
 #define LAUNCH(I)                                                                                   \
   hipLaunchKernelGGL((gather_ln_kernel<XT, I>), grid, block, 0, st, xp, add, rows, n_rows, hidden, \
-                     gain, bias, eps, out)
+                     gain, bias, eps, out, mod)
   if (iters <= 1) LAUNCH(1);
   else if (iters <= 2) LAUNCH(2);
   else if (iters <= 4) LAUNCH(4);
@@ -218,10 +228,10 @@ static hipError_t gather_ln_dispatch(const void* x, const bf16_t* add, const int
 
 hipError_t launch_gather_ln(const void* x, bool x_fp32, const bf16_t* add, const int32_t* rows, int n_rows,
                             int hidden, const bf16_t* gain, const bf16_t* bias, float eps, bf16_t* out,
-                            hipStream_t st) {
+                            hipStream_t st, const LnMod& mod) {
   if (n_rows <= 0) return hipSuccess;
-  return x_fp32 ? gather_ln_dispatch<float>(x, add, rows, n_rows, hidden, gain, bias, eps, out, st)
-                : gather_ln_dispatch<bf16_t>(x, add, rows, n_rows, hidden, gain, bias, eps, out, st);
+  return x_fp32 ? gather_ln_dispatch<float>(x, add, rows, n_rows, hidden, gain, bias, eps, out, mod, st)
+                : gather_ln_dispatch<bf16_t>(x, add, rows, n_rows, hidden, gain, bias, eps, out, mod, st);
 }
 
 // ---------------------------------------------------------------------------------
@@ -408,5 +418,99 @@ hipError_t launch_second_diff_stats(const bf16_t* f_prev, const bf16_t* f_cur, c
                      scratch);
   hipLaunchKernelGGL(second_diff_final_kernel, dim3(1), dim3(64), 0, st, scratch, STAB_BLOCKS, stats,
                      accumulate ? 1 : 0);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------
+// q / k post-processing of the modulated block: LayerNorm over each head's channels (eps 1e-6,
+// one gain / bias vector of head_dim elements shared by the heads), then 3-D rotary positions on
+// video rows, then (q only) the softmax scale.  In place, one wave per row: a lane holds 8
+// consecutive channels = 4 rotation pairs, a head spans head_dim / 8 neighbouring lanes.
+// ---------------------------------------------------------------------------------
+template <int HD>
+__global__ __launch_bounds__(256) void qk_post_kernel(QkPostArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= a.n_rows) return;
+  const int64_t src = a.rows ? (int64_t)a.rows[r] : (int64_t)r;
+  const bool rotate = a.rope != nullptr && src >= a.n_text;
+  const float2* table = rotate ? a.rope + (src - a.n_text) * (HD / 2) : nullptr;
+  const int n_chunks = a.d >> 3;
+#pragma unroll
+  for (int which = 0; which < 2; ++which) {
+    bf16_t* row = which == 0 ? a.q + (int64_t)r * a.d : a.k + src * a.d;
+    const bf16_t* gain = which == 0 ? a.qn_g : a.kn_g;
+    const bf16_t* bias = which == 0 ? a.qn_b : a.kn_b;
+    const float scale = which == 0 ? a.q_scale : 1.0f;
+    for (int c = lane; c < n_chunks; c += 64) {      // whole heads stay inside one pass: 512 % HD == 0
+      float v[8];
+      ResidIO<bf16_t>::load8(row + c * 8, v);
+      const int ch = (c * 8) % HD;                    // first channel of this lane inside its head
+      if (gain != nullptr) {
+        float s = 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) s += v[j];
+#pragma unroll
+        for (int o = 1; o < HD / 8; o <<= 1) s += __shfl_xor(s, o, 64);
+        const float mean = s * (1.0f / HD);
+        float sq = 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { const float dl = v[j] - mean; sq += dl * dl; }
+#pragma unroll
+        for (int o = 1; o < HD / 8; o <<= 1) sq += __shfl_xor(sq, o, 64);
+        const float rstd = rsqrtf(sq * (1.0f / HD) + 1e-6f);
+        float g8[8], b8[8];
+        ResidIO<bf16_t>::load8(gain + ch, g8);
+        ResidIO<bf16_t>::load8(bias + ch, b8);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = (v[j] - mean) * rstd * g8[j] + b8[j];
+      }
+      if (rotate) {
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+          const float2 cs = table[ch / 2 + p];
+          const float x0 = v[2 * p], x1 = v[2 * p + 1];
+          v[2 * p] = x0 * cs.x - x1 * cs.y;
+          v[2 * p + 1] = x0 * cs.y + x1 * cs.x;
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[j] *= scale;
+      ResidIO<bf16_t>::store8(row + c * 8, v);
+    }
+  }
+}
+
+hipError_t launch_qk_post(const QkPostArgs& a, hipStream_t st) {
+  if (a.n_rows <= 0) return hipSuccess;
+  if (a.d % a.head_dim != 0 || (a.head_dim != 32 && a.head_dim != 64)) return hipErrorInvalidValue;
+  dim3 grid((a.n_rows + 3) / 4), block(256);
+  if (a.head_dim == 64) hipLaunchKernelGGL(qk_post_kernel<64>, grid, block, 0, st, a);
+  else hipLaunchKernelGGL(qk_post_kernel<32>, grid, block, 0, st, a);
+  return hipGetLastError();
+}
+
+// (cos, sin) of the rotation angle of every (video token, channel pair); evaluated in fp64
+__global__ void rope_table_kernel(float2* __restrict__ table, int frames, int height, int width, int half_dim) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t n = (int64_t)frames * height * width * half_dim;
+  if (i >= n) return;
+  const int p = (int)(i % half_dim);
+  const int64_t tok = i / half_dim;
+  const int x = (int)(tok % width), y = (int)((tok / width) % height), t = (int)(tok / ((int64_t)width * height));
+  const int n_t = half_dim / 4, n_y = (half_dim / 8) * 3;      // head_dim/8 pairs, 3*head_dim/16 pairs
+  int pos, idx, cnt;
+  if (p < n_t) { pos = t; idx = p; cnt = n_t; }
+  else if (p < n_t + n_y) { pos = y; idx = p - n_t; cnt = n_y; }
+  else { pos = x; idx = p - n_t - n_y; cnt = half_dim - n_t - n_y; }
+  const double angle = (double)pos * pow(10000.0, -(double)idx / (double)cnt);
+  table[i] = make_float2((float)cos(angle), (float)sin(angle));
+}
+
+hipError_t launch_rope_table(float2* table, int frames, int height, int width, int head_dim, hipStream_t st) {
+  const int64_t n = (int64_t)frames * height * width * (head_dim / 2);
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, table, frames, height, width,
+                     head_dim / 2);
   return hipGetLastError();
 }

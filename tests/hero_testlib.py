@@ -20,7 +20,13 @@ def to_host_f64(t: torch.Tensor) -> np.ndarray:
 
 def upload_weights(cache, cfg, weights):
     for l, w in enumerate(weights):
-        cache.hero_set_layer_weights(l, {n: to_dev_bf16(w[n]) for n in WEIGHT_NAMES})
+        dev = {n: to_dev_bf16(w[n]) for n in WEIGHT_NAMES}
+        # extra parameters of the modulated block, under the names the C struct uses
+        for src, dst in (("qn_g", "q_norm_g"), ("qn_b", "q_norm_b"), ("kn_g", "k_norm_g"), ("kn_b", "k_norm_b"),
+                         ("mod", "mod")):
+            if src in w:
+                dev[dst] = to_dev_bf16(w[src])
+        cache.hero_set_layer_weights(l, dev)
 
 
 def error_stats(got: np.ndarray, want: np.ndarray):

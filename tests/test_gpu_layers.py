@@ -10,8 +10,9 @@ import torch
 
 from oracle import hero_oracle as O
 from paper_2508_17588_amd import binding as B
-from workloads import get_config, make_layer_weights, make_tokens, perturb_tokens, euler_update
-from hero_testlib import assert_close, to_host_f64, upload_weights
+from workloads import (get_config, make_block_extras, make_layer_weights, make_tokens, perturb_tokens, euler_update,
+                       BLOCK_ADALN, BLOCK_QKNORM, BLOCK_ROPE)
+from hero_testlib import assert_close, to_dev_bf16, to_host_f64, upload_weights
 
 pytestmark = pytest.mark.gpu
 
@@ -25,6 +26,9 @@ def say(msg):
 
 def make(cfg, std, resid_fp32=True):
     ws = [make_layer_weights(cfg, l, seed=0, std=std, ln_affine_noise=0.1) for l in range(cfg.n_layers)]
+    if cfg.block_flags:
+        for l, w in enumerate(ws):
+            w.update(make_block_extras(cfg, l, seed=0, step=0))
     cache = B.HeroCache(B.make_config(cfg, resid_fp32=resid_fp32))
     upload_weights(cache, cfg, ws)
     orc = O.HeroOracle(cfg, ws)
@@ -50,7 +54,17 @@ def check_layer_caches(cache, orc, layer, cfg, tag):
         assert_close(sp, c.g_attn_prev + c.g_ffn_prev, f"{tag}: S_prev")
 
 
-@pytest.mark.parametrize("base,over,std", [("tiny", {}, 0.05), ("tiny", MID, 0.04)])
+ALL_BLOCK = BLOCK_ADALN | BLOCK_QKNORM | BLOCK_ROPE
+
+
+@pytest.mark.parametrize("base,over,std", [
+    ("tiny", {}, 0.05), ("tiny", MID, 0.04),
+    # the modulated block, one part at a time and all together, at head_dim 32 and 64
+    ("tiny", dict(block_flags=BLOCK_ADALN), 0.05), ("tiny", dict(block_flags=BLOCK_QKNORM), 0.05),
+    ("tiny", dict(block_flags=BLOCK_ROPE), 0.05), ("tiny", dict(block_flags=ALL_BLOCK), 0.05),
+    ("tiny", dict(MID, block_flags=BLOCK_ADALN), 0.04), ("tiny", dict(MID, block_flags=BLOCK_QKNORM), 0.04),
+    ("tiny", dict(MID, block_flags=BLOCK_ROPE), 0.04), ("tiny", dict(MID, block_flags=ALL_BLOCK), 0.04),
+])
 @pytest.mark.parametrize("resid_fp32", [True, False])
 def test_full_then_refresh_then_extrapolate(base, over, std, resid_fp32):
     cfg = get_config(base, **over)
@@ -202,6 +216,12 @@ def run_schedule(cfg, std, n_steps, check_every_step=True):
     worst = (0.0, 0.0)
     for step in range(n_steps):
         say(f"  step {step}")
+        if cfg.block_flags & BLOCK_ADALN:
+            # a new timestep brings a new modulation table: rewritten in place on both sides
+            for l in range(cfg.n_layers):
+                mod = make_block_extras(cfg, l, seed=0, step=step)["mod"]
+                orc.w[l]["mod"] = mod.astype(np.float64)
+                cache._weights[l]["mod"].copy_(to_dev_bf16(mod))
         x_in_d = xd.clone()
         cache.hero_step(xd, step)
         yo = orc.step(xo, step)
@@ -243,6 +263,9 @@ def test_special_schedules():
     run_schedule(get_config("tiny", n_shallow=0, interval=2), 0.05, 5)
     run_schedule(get_config("tiny", n_shallow=2, interval=3), 0.05, 5)
     run_schedule(get_config("tiny", interval=1), 0.05, 3)
+    say("modulated block (adaLN + q/k norm + rotary positions), modulation changing every step")
+    run_schedule(get_config("tiny", block_flags=ALL_BLOCK), 0.05, 9)
+    run_schedule(get_config("tiny", **dict(MID, block_flags=ALL_BLOCK, interval=3)), 0.04, 5)
     say("age-weighted random selection through the whole schedule")
     run_schedule(get_config("tiny", select_mode=1, interval=5, patch_w=3, ratio=0.34), 0.05, 10)
 

@@ -41,7 +41,7 @@ def test_config_struct_layout_matches_header(lib):
     assert ctypes.sizeof(B.hero_config) == 80
     assert B.hero_config.seed.offset == 64
     assert B.hero_config.select_mode.offset == 72
-    assert ctypes.sizeof(B.hero_layer_weights) == 12 * ctypes.sizeof(ctypes.c_void_p)
+    assert ctypes.sizeof(B.hero_layer_weights) == 17 * ctypes.sizeof(ctypes.c_void_p)
 
 
 @pytest.mark.parametrize("name", sorted(CONFIGS))
@@ -88,6 +88,8 @@ def test_invalid_configs_are_rejected(lib):
     assert rc_of(ratio=-0.5) == B.HERO_ERR_INVALID_ARG
     assert rc_of(select_mode=2) == B.HERO_ERR_INVALID_ARG
     assert rc_of(select_mode=1) == B.HERO_OK
+    assert rc_of(block_flags=7) == B.HERO_OK
+    assert rc_of(block_flags=8) == B.HERO_ERR_INVALID_ARG
     assert rc_of(select_mode=1, height=300, width=300, patch_h=256, patch_w=257) == B.HERO_ERR_SHAPE
     assert rc_of(head_dim=48, n_heads=4, hidden=192) == B.HERO_ERR_SHAPE
     assert rc_of(hidden=96, n_heads=3) == B.HERO_ERR_SHAPE           # not a multiple of 64
