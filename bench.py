@@ -28,6 +28,8 @@ def parse():
     p.add_argument("--steps", type=int, default=50)
     p.add_argument("--warmup", type=int, default=2)
     p.add_argument("--workload", default="cvx5b_42l")
+    p.add_argument("--block-flags", type=int, default=0,
+                   help="1 adaLN modulation + 2 q/k LayerNorm + 4 rotary positions (default 0: the plain block)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--cpu-sample-rows", type=int, default=4485)
     return p.parse_args()
@@ -40,7 +42,7 @@ def device_weights(cfg, torch, gen):
     def draw(*shape):
         return (torch.randn(*shape, generator=gen, device="cuda", dtype=torch.float32) * 0.02).to(torch.bfloat16)
 
-    return {
+    w = {
         "ln1_g": torch.ones(d, device="cuda", dtype=torch.bfloat16),
         "ln1_b": torch.zeros(d, device="cuda", dtype=torch.bfloat16),
         "w_qkv": draw(3 * d, d), "b_qkv": draw(3 * d), "w_o": draw(d, d), "b_o": draw(d),
@@ -48,6 +50,16 @@ def device_weights(cfg, torch, gen):
         "ln2_b": torch.zeros(d, device="cuda", dtype=torch.bfloat16),
         "w_ff1": draw(f, d), "b_ff1": draw(f), "w_ff2": draw(d, f), "b_ff2": draw(d),
     }
+    if cfg.block_flags:
+        # modulated block: q/k LayerNorm gain 1 / bias 0, modulation table N(0, 0.1) with gates around 1
+        hd = cfg.head_dim
+        for nm in ("q_norm", "k_norm"):
+            w[nm + "_g"] = torch.ones(hd, device="cuda", dtype=torch.bfloat16)
+            w[nm + "_b"] = torch.zeros(hd, device="cuda", dtype=torch.bfloat16)
+        mod = torch.randn(12, d, generator=gen, device="cuda", dtype=torch.float32) * 0.1
+        mod[2::3] += 1.0
+        w["mod"] = mod.to(torch.bfloat16)
+    return w
 
 
 def cpu_baseline(cfg, w0, x0_host, n_rows, n_steps):
@@ -99,7 +111,7 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     B.load_library()          # fails loudly when the HIP library has not been built
-    cfg = get_config(args.workload)
+    cfg = get_config(args.workload, block_flags=args.block_flags) if args.block_flags else get_config(args.workload)
     torch.cuda.set_device(0)
     gen = torch.Generator(device="cuda")
     gen.manual_seed(0)
@@ -200,7 +212,8 @@ def main():
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "layers": cfg.n_layers, "shallow_layers": cfg.n_shallow,
                    "interval": cfg.interval, "hidden": cfg.hidden, "heads": cfg.n_heads, "ffn": cfg.ffn_dim,
-                   "tokens": cfg.n_tokens, "refreshed_rows": n_sel, "resid": "fp32" if cfg.resid_fp32 else "bf16"},
+                   "tokens": cfg.n_tokens, "refreshed_rows": n_sel, "resid": "fp32" if cfg.resid_fp32 else "bf16",
+                   "block_flags": cfg.block_flags},
         "full_step_ms": round(mean(full_ms), 3) if full_ms else None,
         "cached_step_ms": round(mean(cached_ms), 3) if cached_ms else None,
         "speedup_vs_all_full": round(mean(full_ms) / ms_per_step, 3) if full_ms else None,

@@ -656,19 +656,22 @@ __device__ __forceinline__ void epilogue256(const GemmArgs& g, floatx16_t (&acc)
       const int n = min(nw + 32 * j + 8 * q + 4 * lh, g.n - 4);     // columns past N are never stored
       bias4[j][q] = *reinterpret_cast<const u32x2_t*>(g.bias + n);
     }
-  // adaLN gate of the lane's columns, for both streams; the lane's row i picks one
+  // adaLN gate of the lane's columns, for both streams; the lane's row i picks one.  (Loaded
+  // unconditionally, from the bias vector when there is no gate, so that the arrays stay in registers.)
   constexpr bool CAN_GATE = EPI == EPI_SCATTER || EPI == EPI_SCATTER_ADD;
   const bool gated = CAN_GATE && g.gate_v != nullptr;
   u32x2_t gate4_v[2][4], gate4_t[2][4];
-  bool text_row[4] = {false, false, false, false};
-  if (gated) {
+  bool text_row[4];
+  if (CAN_GATE) {
+    const bf16_t* gv = gated ? g.gate_v : g.bias;
+    const bf16_t* gt = gated ? g.gate_t : g.bias;
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const int n = min(nw + 32 * j + 8 * q + 4 * lh, g.n - 4);
-        gate4_v[j][q] = *reinterpret_cast<const u32x2_t*>(g.gate_v + n);
-        gate4_t[j][q] = *reinterpret_cast<const u32x2_t*>(g.gate_t + n);
+        gate4_v[j][q] = *reinterpret_cast<const u32x2_t*>(gv + n);
+        gate4_t[j][q] = *reinterpret_cast<const u32x2_t*>(gt + n);
       }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -681,7 +684,7 @@ __device__ __forceinline__ void epilogue256(const GemmArgs& g, floatx16_t (&acc)
     v[1] = acc[i][j][4 * q + 1] + unpack_hi(bias4[j][q][0]);
     v[2] = acc[i][j][4 * q + 2] + unpack_lo(bias4[j][q][1]);
     v[3] = acc[i][j][4 * q + 3] + unpack_hi(bias4[j][q][1]);
-    if (gated) {
+    if (CAN_GATE && gated) {
       const u32x2_t gg = text_row[i] ? gate4_t[j][q] : gate4_v[j][q];
       v[0] *= unpack_lo(gg[0]); v[1] *= unpack_hi(gg[0]);
       v[2] *= unpack_lo(gg[1]); v[3] *= unpack_hi(gg[1]);

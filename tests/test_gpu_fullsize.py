@@ -12,7 +12,8 @@ import torch
 
 from oracle import hero_oracle as O
 from paper_2508_17588_amd import binding as B
-from workloads import RATIO_SWEEP, get_config, make_layer_weights, make_tokens, perturb_tokens
+from workloads import (RATIO_SWEEP, BLOCK_ADALN, BLOCK_QKNORM, BLOCK_ROPE, get_config, make_block_extras,
+                       make_layer_weights, make_tokens, perturb_tokens)
 from hero_testlib import assert_close, to_host_f64, upload_weights
 
 pytestmark = pytest.mark.gpu
@@ -32,20 +33,38 @@ class BlockOracle:
         self.wq, self.bq = self.w["w_qkv"][:d], self.w["b_qkv"][:d]
         self.wkv, self.bkv = self.w["w_qkv"][d:], self.w["b_qkv"][d:]
 
-    def kv(self, x_rows):
-        u = O.layer_norm(x_rows, self.w["ln1_g"], self.w["ln1_b"], self.cfg.ln_eps)
-        kv = O.linear(u, self.wkv, self.bkv)
-        d = self.cfg.hidden
-        return kv[:, :d], kv[:, d:]
+        self.ext = O.BlockExt(cfg) if cfg.block_flags else None      # the modulated block's parts, if any
 
-    def rows(self, x_rows, k_all, v_all):
+    def kv(self, x_rows, rows):
+        """K, V of the input rows x_rows, which sit at joint-sequence rows `rows`."""
+        d = self.cfg.hidden
+        if self.ext is None:
+            u = O.layer_norm(x_rows, self.w["ln1_g"], self.w["ln1_b"], self.cfg.ln_eps)
+            kv = O.linear(u, self.wkv, self.bkv)
+            return kv[:, :d], kv[:, d:]
+        u = self.ext.ln(x_rows, rows, self.w, 1, self.cfg.ln_eps)
+        kv = O.linear(u, self.wkv, self.bkv)
+        # (q is not needed here: normalise / rotate k alone by passing it as both arguments)
+        _, k = self.ext.qk(kv[:, :d], kv[:, :d], rows, {**self.w, "qn_g": self.w.get("kn_g"), "qn_b": self.w.get("kn_b")})
+        return k, kv[:, d:]
+
+    def rows(self, x_rows, rows, k_all, v_all):
         """(g_attn, g_ffn) of the given input rows against the given keys/values (Eq. 2 / Eq. 3)."""
         c, w = self.cfg, self.w
-        u = O.layer_norm(x_rows, w["ln1_g"], w["ln1_b"], c.ln_eps)
+        if self.ext is None:
+            u = O.layer_norm(x_rows, w["ln1_g"], w["ln1_b"], c.ln_eps)
+            q = O.linear(u, self.wq, self.bq)
+            g_attn = O.linear(O.attention(q, k_all, v_all, c.n_heads), w["w_o"], w["b_o"])
+            a = x_rows + g_attn
+            g_ffn = O.ffn(O.layer_norm(a, w["ln2_g"], w["ln2_b"], c.ln_eps), w)
+            return g_attn, g_ffn
+        e = self.ext
+        u = e.ln(x_rows, rows, w, 1, c.ln_eps)
         q = O.linear(u, self.wq, self.bq)
-        g_attn = O.linear(O.attention(q, k_all, v_all, c.n_heads), w["w_o"], w["b_o"])
+        q, _ = e.qk(q, q, rows, {**w, "kn_g": w.get("qn_g"), "kn_b": w.get("qn_b")})
+        g_attn = e.gate(O.linear(O.attention(q, k_all, v_all, c.n_heads), w["w_o"], w["b_o"]), rows, w, 1)
         a = x_rows + g_attn
-        g_ffn = O.ffn(O.layer_norm(a, w["ln2_g"], w["ln2_b"], c.ln_eps), w)
+        g_ffn = e.gate(O.ffn(e.ln(a, rows, w, 2, c.ln_eps), w), rows, w, 2)
         return g_attn, g_ffn
 
 
@@ -59,16 +78,20 @@ def sample_rows(cfg, idx, rng, n_each=20):
     return sel, np.unique(non), text
 
 
-def run_block(base_name, sweeps, check_all_rows=False):
-    base = get_config(base_name).with_(n_layers=1, n_shallow=1)
+def run_block(base_name, sweeps, check_all_rows=False, block_flags=0, feature_tol=2e-2):
+    """feature_tol: per-element bound of the cached features and of x's increment (K, V keep 2e-2)."""
+    base = get_config(base_name).with_(n_layers=1, n_shallow=1, block_flags=block_flags)
     rng = np.random.default_rng(5)
     w = make_layer_weights(base, 0, seed=0)
+    if block_flags:
+        w.update(make_block_extras(base, 0, seed=0, step=0))
     orc = BlockOracle(base, w)
     x0 = make_tokens(base, seed=1)
     x1 = perturb_tokens(x0, seed=2, std=0.1)
     x0_64, x1_64 = x0.astype(np.float64), x1.astype(np.float64)
     say(f"{base_name}: oracle K/V of all {base.n_tokens} rows")
-    k0, v0 = orc.kv(x0_64)
+    all_rows = np.arange(base.n_tokens)
+    k0, v0 = orc.kv(x0_64, all_rows)
 
     for tag, over in sweeps:
         cfg = base.with_(**over)
@@ -85,11 +108,12 @@ def run_block(base_name, sweeps, check_all_rows=False):
         assert float(np.abs(vt[:, cfg.n_tokens:]).max(initial=0.0)) == 0.0
         del vt
         probe = np.unique(np.concatenate([rng.choice(cfg.n_tokens, 24, replace=False), [0, cfg.n_tokens - 1]]))
-        ga, gf = orc.rows(x0_64[probe], k0, v0)
+        ga, gf = orc.rows(x0_64[probe], probe, k0, v0)
         s_gpu = cache.hero_cache_view(0, B.VIEW_S_CUR)
-        assert_close(to_host_f64(s_gpu[probe]), ga + gf, f"{tag} fill: S rows")
+        # (the attention feature is stored in bf16 before the FFN feature is added to it)
+        assert_close(to_host_f64(s_gpu[probe]), ga + gf, f"{tag} fill: S rows", stored_parts=[ga], max_abs=feature_tol)
         # x is updated in fp32 by the stored (bf16) feature sum: judge the increment at its own scale
-        assert_close(to_host_f64(xd[probe]) - x0_64[probe], ga + gf, f"{tag} fill: x increment rows")
+        assert_close(to_host_f64(xd[probe]) - x0_64[probe], ga + gf, f"{tag} fill: x increment rows", stored_parts=[ga], max_abs=feature_tol)
 
         # --- the cached step: select (bit-exact, in full), refresh
         if tag == "100":
@@ -111,7 +135,7 @@ def run_block(base_name, sweeps, check_all_rows=False):
         torch.cuda.synchronize()
         rows64 = idx_np.astype(np.int64)
         k1, v1 = k0.copy(), v0.copy()
-        k1[rows64], v1[rows64] = orc.kv(x1_64[rows64])
+        k1[rows64], v1[rows64] = orc.kv(x1_64[rows64], rows64)
         assert_close(to_host_f64(cache.hero_cache_view(0, B.VIEW_K)), k1, f"{tag} refresh: K")
         assert_close(to_host_f64(cache.hero_cache_view(0, B.VIEW_VT))[:, :cfg.n_tokens].T, v1, f"{tag} refresh: V")
         if tag == "100":
@@ -119,17 +143,19 @@ def run_block(base_name, sweeps, check_all_rows=False):
             non, text = np.zeros(0, np.int64), np.zeros(0, np.int64)
         else:
             sel, non, text = sample_rows(cfg, idx_np, rng)
-        ga, gf = orc.rows(x1_64[sel], k1, v1)
-        assert_close(to_host_f64(s_gpu[sel]), ga + gf, f"{tag} refresh: S of refreshed rows")
-        assert_close(to_host_f64(xd[sel]) - x1_64[sel], ga + gf, f"{tag} refresh: x increment of refreshed rows")
+        ga, gf = orc.rows(x1_64[sel], sel, k1, v1)
+        assert_close(to_host_f64(s_gpu[sel]), ga + gf, f"{tag} refresh: S of refreshed rows", stored_parts=[ga], max_abs=feature_tol)
+        assert_close(to_host_f64(xd[sel]) - x1_64[sel], ga + gf, f"{tag} refresh: x increment of refreshed rows",
+                     stored_parts=[ga], max_abs=feature_tol)
         keep = np.concatenate([non, text]).astype(np.int64)
         if len(keep):
             assert torch.equal(s_gpu[keep], s_before[keep])             # reused rows untouched
             want = x1_64[keep] + to_host_f64(s_before[keep])
             np.testing.assert_allclose(to_host_f64(xd[keep]), want, rtol=0, atol=2e-6)
             # and those reused features are the full step's: check against the oracle too
-            ga0, gf0 = orc.rows(x0_64[keep], k0, v0)
-            assert_close(to_host_f64(xd[keep]) - x1_64[keep], ga0 + gf0, f"{tag} refresh: x increment of reused rows")
+            ga0, gf0 = orc.rows(x0_64[keep], keep, k0, v0)
+            assert_close(to_host_f64(xd[keep]) - x1_64[keep], ga0 + gf0, f"{tag} refresh: x increment of reused rows",
+                         stored_parts=[ga0], max_abs=feature_tol)
         cache.close()
         del cache, s_gpu, s_before, xd
         torch.cuda.empty_cache()
@@ -144,6 +170,18 @@ def test_cvx5b_block_ratio_sweep():
     """Config 3: one CogVideoX-5B-shaped block, refresh ratio 10 / 25 / 50 / 100 %."""
     run_block("cvx5b_block", [("10", RATIO_SWEEP["10"]), ("25", RATIO_SWEEP["25"]),
                               ("50", RATIO_SWEEP["50"]), ("100", {})])
+
+
+def test_cvx5b_block_modulated():
+    """Config 3's block with adaLN modulation, q/k LayerNorm and rotary positions, 25 % refresh.
+
+    The gates and (1 + scale) factors (1 + N(0, 0.1) per channel, so up to about 1.3) multiply the
+    branch features and with them the absolute error of the bf16 pipeline: measured rms error of the
+    stored feature 4.9e-3 against 4.7e-3 for the plain block, whose worst sampled element already
+    sits at 0.85-0.93 of the 2e-2 bound.  The per-element bound of the features is therefore
+    2.5e-2 here (K and V keep 2e-2, the mean-relative bound stays 5e-3; measured 2.9e-3)."""
+    run_block("cvx5b_block", [("25", RATIO_SWEEP["25"])], block_flags=BLOCK_ADALN | BLOCK_QKNORM | BLOCK_ROPE,
+              feature_tol=2.5e-2)
 
 
 def test_cvx5b_long_video_refresh_and_extrapolation():
@@ -166,9 +204,9 @@ def test_cvx5b_long_video_refresh_and_extrapolation():
     # the cached generations themselves: sampled rows against the oracle
     orc = BlockOracle(cfg, w[1])
     x3 = perturb_tokens(x0, seed=3, std=0.1).astype(np.float64)
-    k3, v3 = orc.kv(x3)
+    k3, v3 = orc.kv(x3, np.arange(cfg.n_tokens))
     probe = np.array([0, 225, 226, 5000, 20000, cfg.n_tokens - 1])
-    ga, gf = orc.rows(x3[probe], k3, v3)
+    ga, gf = orc.rows(x3[probe], probe, k3, v3)
     assert_close(s_cur[probe], ga + gf, "deep layer: S_cur rows")
     x2 = perturb_tokens(x0, seed=4, std=0.1)
     xd = torch.from_numpy(x2).cuda()
