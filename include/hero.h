@@ -226,6 +226,16 @@ int hero_attention(const void* dev_q, const void* dev_k, const void* dev_vt, int
                    void* dev_o, int32_t r, int32_t n_keys, int32_t n_heads, int32_t head_dim,
                    void* stream);
 
+/* The same attention, computed the way the layer entry points compute theirs: with device scratch
+ * (caller-owned, 16-byte aligned; 128 MiB lets every problem use it) the query blocks of the last,
+ * partly filled round of workgroups are cut along the keys (head_dim 64 only); their unnormalised
+ * partial outputs and row sums pass through the scratch and a second kernel adds them up,
+ * normalises and stores.  The result differs from hero_attention's only by the order of the fp32
+ * additions.  Calls that share a scratch buffer must not overlap. */
+int hero_attention_scratch(const void* dev_q, const void* dev_k, const void* dev_vt, int64_t ld_vt,
+                           void* dev_o, int32_t r, int32_t n_keys, int32_t n_heads, int32_t head_dim,
+                           void* dev_scratch, size_t scratch_bytes, void* stream);
+
 /* x[N,hidden] += (1+alpha) * s_cur - alpha * s_prev (Eq. 5 followed by the residual add);
  * s_prev may be NULL (alpha is then ignored: plain x += s_cur, Eq. 3's merge-and-add). */
 int hero_axpy_features(void* dev_x, int32_t x_dtype, const void* s_cur, const void* s_prev,

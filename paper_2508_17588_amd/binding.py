@@ -39,7 +39,7 @@ EXPORTS = (
     "hero_cache_destroy", "hero_cache_reset", "hero_set_layer_weights", "hero_full_layer",
     "hero_select", "hero_reset_ages", "hero_refresh_layer", "hero_extrapolate_layer", "hero_step",
     "hero_cache_view", "hero_cache_state", "hero_profile_begin", "hero_profile_begin_kinds", "hero_profile_end", "hero_gather_ln", "hero_linear", "hero_linear_scratch",
-    "hero_attention",
+    "hero_attention", "hero_attention_scratch",
     "hero_axpy_features", "hero_second_diff_stats", "hero_stability_scores",
 )
 
@@ -100,6 +100,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
         "hero_linear": [P, P, P, P, I, I, I, I, P],
         "hero_linear_scratch": [P, P, P, P, I, I, I, I, P, ctypes.c_size_t, P],
         "hero_attention": [P, P, P, c_int64, P, I, I, I, I, P],
+        "hero_attention_scratch": [P, P, P, c_int64, P, I, I, I, I, P, ctypes.c_size_t, P],
         "hero_axpy_features": [P, I, P, P, c_float, c_int64, P],
         "hero_second_diff_stats": [P, P, P, c_int64, P, ctypes.c_size_t, P, I, P],
         "hero_stability_scores": [POINTER(ctypes.c_double), I, POINTER(ctypes.c_double)],
@@ -328,7 +329,8 @@ def hero_linear_scratch(a, w, bias, c, scratch, act: int = 0):
                                               scratch.numel() * scratch.element_size(), _stream()))
 
 
-def hero_attention(q, k, vt, o, n_keys: int, n_heads: int, head_dim: int):
+def hero_attention(q, k, vt, o, n_keys: int, n_heads: int, head_dim: int, scratch=None):
+    """scratch: optional contiguous device tensor; with it the call goes through hero_attention_scratch."""
     import torch
     for t, n in ((q, "q"), (k, "k"), (vt, "vt"), (o, "o")):
         _need(t, torch.bfloat16, n)
@@ -336,6 +338,11 @@ def hero_attention(q, k, vt, o, n_keys: int, n_heads: int, head_dim: int):
     d = n_heads * head_dim
     if q.shape[1] != d or k.shape[1] != d or k.shape[0] < n_keys or vt.shape[0] != d or o.numel() < r * d:
         raise ValueError("shape mismatch")
+    if scratch is not None:
+        _check(load_library().hero_attention_scratch(_ptr(q), _ptr(k), _ptr(vt), vt.shape[1], _ptr(o), r, n_keys,
+                                                     n_heads, head_dim, _ptr(scratch),
+                                                     scratch.numel() * scratch.element_size(), _stream()))
+        return
     _check(load_library().hero_attention(_ptr(q), _ptr(k), _ptr(vt), vt.shape[1], _ptr(o), r, n_keys,
                                          n_heads, head_dim, _stream()))
 

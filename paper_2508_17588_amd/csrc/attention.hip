@@ -38,6 +38,8 @@
 //    than 2^8, one 64-key tile at a time, register-staged double-buffered LDS.
 #include <type_traits>
 
+#include <algorithm>
+
 #include "hero_device.h"
 #include "hero_kernels.h"
 
@@ -297,17 +299,47 @@ __device__ __forceinline__ void direct_lds_load(u32x4_t rsrc, uint32_t lds_base,
                :: "s"(lds_base), "v"(voffset), "s"(rsrc) : "memory");
 }
 
+// Split of the last, partly filled round of workgroups along the keys.  Block slots
+// 0 .. full_items-1 are whole work items; every later slot is cut into `split` key ranges whose
+// unnormalised outputs and row sums (the reference-free form needs no common maximum, so they
+// simply add) go to a workspace, one block of PART_FLOATS floats per range, in accumulator
+// order; the fix-up kernel adds them, checks the row sums, normalises and stores.
+struct KeySplit {
+  int32_t full_items;
+  int32_t split;       // key ranges per remaining slot (1: none)
+  float* ws;
+};
+constexpr int PART_FLOATS = 256 * 66;      // per thread: 64 output values and 2 row sums
+
+template <int NW>
+__device__ __forceinline__ void attention_finish(const AttnArgs& a, int head, int q0, int wave, int lane,
+                                                 floatx16_t (&o)[2][2], const float (&l)[2], char* lds);
+
 template <int NW>
 __global__ __launch_bounds__(NW * 64, 2) void attention_hd64_kernel(AttnArgs a, int n_qblocks, int n_blocks,
-                                                                    int per_xcd) {
+                                                                    int per_xcd, KeySplit ks) {
   constexpr int HD = 64;
   constexpr int NL = 8 / NW;              // 1 KB wave-loads per wave per tile (K and V^T each)
   static_assert(8 % NW == 0, "waves must divide the 8 wave-loads of a tile");
 
-  int logical = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  int slot = blockIdx.x, chunk = 0, n_chunks = 1;
+  if (slot >= ks.full_items) {
+    const int rr = slot - ks.full_items;
+    slot = ks.full_items + rr / ks.split;
+    chunk = rr - (rr / ks.split) * ks.split;
+    n_chunks = ks.split;
+  }
+  int logical = (slot % 8) * per_xcd + slot / 8;
   if (logical >= n_blocks) return;
   const int head = logical / n_qblocks, qb = logical % n_qblocks;
   const int d = a.n_heads * HD;
+  // this item's keys: whole 64-key tiles [t_begin, t_end) of the problem; the last range also takes the ragged tail
+  const int tiles_all = a.n_keys / BKV;
+  const int t_begin = (int)((int64_t)chunk * tiles_all / n_chunks);
+  const int t_end = (int)((int64_t)(chunk + 1) * tiles_all / n_chunks);
+  const int n_keys = (chunk == n_chunks - 1) ? a.n_keys - t_begin * BKV : (t_end - t_begin) * BKV;
+  const bf16_t* kbase = a.k + (int64_t)t_begin * BKV * d;
+  const bf16_t* vtbase = a.vt + (int64_t)t_begin * BKV;
 
   __shared__ u32x4_t skv[2][3][TILE];            // K tiles, then V^T tiles, three rotating buffers each
   u32x4_t (&sK)[3][TILE] = skv[0];
@@ -336,10 +368,10 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_hd64_kernel(AttnArgs a, 
 
   // ---- staging: wave-load j (of 8) fills tile rows 8j..8j+7; lane l -> row 8j + l/8 and LDS
   //      chunk slot l%8, which holds the row's logical chunk (l%8) ^ ((row>>1)&7) ----
-  const uint32_t k_bytes = (uint32_t)((int64_t)a.n_keys * d * 2 - head * HD * 2);
-  const uint32_t v_bytes = (uint32_t)(((int64_t)d - head * HD) * a.ld_vt * 2);
-  const u32x4_t rsK = make_rsrc_words(a.k + head * HD, k_bytes);
-  const u32x4_t rsV = make_rsrc_words(a.vt + (int64_t)head * HD * a.ld_vt, v_bytes);
+  const uint32_t k_bytes = (uint32_t)((int64_t)n_keys * d * 2 - head * HD * 2);
+  const uint32_t v_bytes = (uint32_t)(((int64_t)d - head * HD) * a.ld_vt * 2 - (int64_t)t_begin * BKV * 2);
+  const u32x4_t rsK = make_rsrc_words(kbase + head * HD, k_bytes);
+  const u32x4_t rsV = make_rsrc_words(vtbase + (int64_t)head * HD * a.ld_vt, v_bytes);
   // LDS byte address of this wave's first 1 KB slot in buffer 0 (wave-uniform)
   const uint32_t lds_k0 = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)(lds_ptr_t)&sK[0][64 * wave]);
   const uint32_t lds_v0 = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)(lds_ptr_t)&sV[0][64 * wave]);
@@ -449,7 +481,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_hd64_kernel(AttnArgs a, 
     }
   };
 
-  const int ntf = a.n_keys / BKV;         // full key tiles; 32-key blocks 0 .. 2*ntf-1
+  const int ntf = n_keys / BKV;           // full key tiles; 32-key blocks 0 .. 2*ntf-1
   if (ntf > 0) {
     // ---- prologue: scores of blocks 0 and 1, probabilities of block 0 ----
     gload_k(0, 0); gload_v(0, 0); gload_k(1, 1); gload_v(1, 1); gload_k(2, 2);
@@ -527,7 +559,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_hd64_kernel(AttnArgs a, 
   }
 
   // ---- ragged tail: keys ntf*64 .. n_keys-1 (K rows past the end arrive as zero and are masked) ----
-  const int n_tail = a.n_keys - ntf * BKV;
+  const int n_tail = n_keys - ntf * BKV;
   if (n_tail > 0) {
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
@@ -553,26 +585,91 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_hd64_kernel(AttnArgs a, 
 
   __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): no LDS fill of this wave is still in flight
 
-  // ---- row sums; were the scores inside the range of the reference-free form? ----
+  // ---- row sums ----
   float l[2];
-  int bad = 0;
 #pragma unroll
   for (int ig = 0; ig < 2; ++ig) {
     l[ig] = la[ig] + lb[ig];
     l[ig] += __shfl_xor(l[ig], 32, 64);   // the two key halves of the query
-    bad |= !(l[ig] >= 0x1p-80f && l[ig] <= 0x1p80f);
   }
+  if (n_chunks > 1) {
+    // partial result of a key range: 1 KB per store instruction, contiguous over the workgroup
+    float* part = ks.ws + ((size_t)(slot - ks.full_items) * ks.split + chunk) * PART_FLOATS;
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+      for (int ig = 0; ig < 2; ++ig)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          floatx4_t v = {o[cb][ig][4 * q], o[cb][ig][4 * q + 1], o[cb][ig][4 * q + 2], o[cb][ig][4 * q + 3]};
+          *reinterpret_cast<floatx4_t*>(part + (((cb * 2 + ig) * 4 + q) * 256 + tid) * 4) = v;
+        }
+    part[64 * 256 + tid] = l[0];
+    part[65 * 256 + tid] = l[1];
+    return;
+  }
+  // were the scores inside the range of the reference-free form?
+  const int bad = !(l[0] >= 0x1p-80f && l[0] <= 0x1p80f) | !(l[1] >= 0x1p-80f && l[1] <= 0x1p80f);
   if (__syncthreads_or(bad)) {
     attention_general<HD, NW>(a, head, q0, a.q_scale, &sK[0][0], &sV[0][0]);
     return;
   }
+  attention_finish<NW>(a, head, q0, wave, lane, o, l, reinterpret_cast<char*>(&skv[0][0][0]));
+}
 
+// Adds up the key ranges of a split query block (one workgroup per block, same thread -> element
+// mapping as the main kernel), then finishes it like an unsplit one.
+template <int NW>
+__global__ __launch_bounds__(NW * 64, 2) void attention_hd64_fixup_kernel(AttnArgs a, int n_qblocks, int n_blocks,
+                                                                          int per_xcd, KeySplit ks) {
+  constexpr int HD = 64;
+  const int slot = ks.full_items + blockIdx.x;
+  const int logical = (slot % 8) * per_xcd + slot / 8;
+  if (logical >= n_blocks) return;
+  const int head = logical / n_qblocks, qb = logical % n_qblocks;
+  __shared__ u32x4_t skv[2][3][TILE];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int q0 = qb * (NW * 64) + wave * 64;
+  floatx16_t o[2][2];
+  float l[2] = {0.f, 0.f};
+#pragma unroll
+  for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+    for (int ig = 0; ig < 2; ++ig)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) o[cb][ig][e] = 0.f;
+  const float* part = ks.ws + (size_t)blockIdx.x * ks.split * PART_FLOATS;
+  for (int c = 0; c < ks.split; ++c, part += PART_FLOATS) {
+    floatx4_t v[16];
+#pragma unroll
+    for (int x = 0; x < 16; ++x) v[x] = __builtin_nontemporal_load(reinterpret_cast<const floatx4_t*>(part + (x * 256 + tid) * 4));
+#pragma unroll
+    for (int x = 0; x < 16; ++x)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[x >> 3][(x >> 2) & 1][4 * (x & 3) + e] += v[x][e];
+    l[0] += part[64 * 256 + tid];
+    l[1] += part[65 * 256 + tid];
+  }
+  const int bad = !(l[0] >= 0x1p-80f && l[0] <= 0x1p80f) | !(l[1] >= 0x1p-80f && l[1] <= 0x1p80f);
+  if (__syncthreads_or(bad)) {
+    attention_general<HD, NW>(a, head, q0, a.q_scale, &skv[0][0][0], &skv[1][0][0]);
+    return;
+  }
+  attention_finish<NW>(a, head, q0, wave, lane, o, l, reinterpret_cast<char*>(&skv[0][0][0]));
+}
+
+template <int NW>
+__device__ __forceinline__ void attention_finish(const AttnArgs& a, int head, int q0, int wave, int lane,
+                                                 floatx16_t (&o)[2][2], const float (&l)[2], char* lds) {
+  constexpr int HD = 64;
+  const int d = a.n_heads * HD;
+  const int lr = lane & 31, lh = lane >> 5;
   // ---- normalise; the wave's 64 x 64 block goes through LDS (the K/V buffers are idle now: every
   //      wave passed the barrier above after its last fragment read) so that each query's 128-byte
   //      output row leaves as one full cache line: lane owns query column lr, channels 8q + 4lh + e ----
   constexpr int OST = 136;                       // staging row stride in bytes (128 + 8: conflict-free 8-byte writes)
-  static_assert(NW * 64 * OST <= (int)sizeof(skv), "output staging must fit the K/V buffers");
-  char* stage = reinterpret_cast<char*>(&skv[0][0][0]) + wave * (64 * OST);
+  static_assert(NW * 64 * OST <= 2 * 3 * TILE * 16, "output staging must fit the K/V buffers");
+  char* stage = lds + wave * (64 * OST);
 #pragma unroll
   for (int ig = 0; ig < 2; ++ig) {
     const float inv = 1.0f / l[ig];
@@ -604,10 +701,34 @@ hipError_t launch_cfg(const AttnArgs& a, hipStream_t st) {
   int n_qblocks = (a.r + NW * 64 - 1) / (NW * 64);
   int n_blocks = n_qblocks * a.n_heads;
   int per_xcd = (n_blocks + 7) / 8;
-  if (HD == 64)
-    hipLaunchKernelGGL((attention_hd64_kernel<NW>), dim3(per_xcd * 8), dim3(NW * 64), 0, st, a, n_qblocks, n_blocks,
-                       per_xcd);
-  else
+  if (HD == 64) {
+    // The chip runs 512 of these workgroups at a time (two per CU).  The n_rem blocks of the last
+    // round are cut into s key ranges so that the round takes ceil(n_rem*s/512)/s of a block's
+    // time (plus about two key tiles of pipeline fill per range); s minimises that.
+    KeySplit ks;
+    const int slots = per_xcd * 8;
+    ks.full_items = slots / 512 * 512;
+    ks.split = 1;
+    ks.ws = a.split_ws;
+    const int n_rem = slots - ks.full_items;
+    const int key_tiles = a.n_keys / BKV;
+    if (a.split_ws != nullptr && n_rem > 0) {
+      const int s_max = (int)std::min<size_t>((size_t)std::min(key_tiles / 16, 16),
+                                              a.split_ws_bytes / ((size_t)n_rem * PART_FLOATS * sizeof(float)));
+      double best = 1.0;
+      for (int sp = 2; sp <= s_max; ++sp) {
+        const double t = (double)((n_rem * sp + 511) / 512) / sp * (1.0 + 2.0 * sp / key_tiles) + 0.004 * sp;
+        if (t < best - 0.02) { best = t; ks.split = sp; }
+      }
+    }
+    if (ks.split == 1) ks.full_items = slots;
+    const int n_split = slots - ks.full_items;
+    hipLaunchKernelGGL((attention_hd64_kernel<NW>), dim3(ks.full_items + n_split * ks.split), dim3(NW * 64), 0, st, a,
+                       n_qblocks, n_blocks, per_xcd, ks);
+    if (n_split > 0)
+      hipLaunchKernelGGL((attention_hd64_fixup_kernel<NW>), dim3(n_split), dim3(NW * 64), 0, st, a, n_qblocks,
+                         n_blocks, per_xcd, ks);
+  } else
     hipLaunchKernelGGL((attention_general_kernel<HD, NW>), dim3(per_xcd * 8), dim3(NW * 64), 0, st, a, n_qblocks,
                        n_blocks, per_xcd);
   return hipGetLastError();

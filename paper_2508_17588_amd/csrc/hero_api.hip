@@ -291,6 +291,7 @@ int run_block_rows(hero_cache_t c, LayerState& ls, void* x, const int32_t* rows,
   at.q = c->q; at.k = k_dst; at.vt = vt_dst; at.ld_vt = c->lay.n_pad; at.o = c->o;
   at.r = n_rows; at.n_keys = (int)c->lay.n_tokens; at.n_heads = cfg.n_heads; at.head_dim = cfg.head_dim;
   at.q_scale = 1.0f;
+  at.split_ws = c->splitk; at.split_ws_bytes = c->lay.splitk_bytes;    // shared with the GEMMs: same stream, never concurrent
   PROF_LAUNCH(c, HERO_PROF_ATTN, 4.0 * rd * n_all, st, launch_attention(at, st));
 
   memset(&g, 0, sizeof(g));
@@ -718,8 +719,9 @@ int hero_linear(const void* dev_a, const void* dev_w, const void* dev_bias, void
   return hero_linear_scratch(dev_a, dev_w, dev_bias, dev_c, m, n, k, act, nullptr, 0, stream);
 }
 
-int hero_attention(const void* dev_q, const void* dev_k, const void* dev_vt, int64_t ld_vt, void* dev_o,
-                   int32_t r, int32_t n_keys, int32_t n_heads, int32_t head_dim, void* stream) {
+int hero_attention_scratch(const void* dev_q, const void* dev_k, const void* dev_vt, int64_t ld_vt, void* dev_o,
+                           int32_t r, int32_t n_keys, int32_t n_heads, int32_t head_dim, void* dev_scratch,
+                           size_t scratch_bytes, void* stream) {
   if (!dev_q || !dev_k || !dev_vt || !dev_o) return fail(HERO_ERR_INVALID_ARG, "null pointer");
   if (r < 0 || n_keys < 1 || n_heads < 1) return fail(HERO_ERR_INVALID_ARG, "bad sizes");
   if (head_dim != 32 && head_dim != 64) return fail(HERO_ERR_SHAPE, "head_dim must be 32 or 64");
@@ -728,8 +730,15 @@ int hero_attention(const void* dev_q, const void* dev_k, const void* dev_vt, int
   a.q = (const bf16_t*)dev_q; a.k = (const bf16_t*)dev_k; a.vt = (const bf16_t*)dev_vt; a.ld_vt = ld_vt;
   a.o = (bf16_t*)dev_o; a.r = r; a.n_keys = n_keys; a.n_heads = n_heads; a.head_dim = head_dim;
   a.q_scale = 1.4426950408889634f / sqrtf((float)head_dim);
+  if (dev_scratch != nullptr && (uintptr_t)dev_scratch % 16 != 0) return fail(HERO_ERR_INVALID_ARG, "scratch must be 16-byte aligned");
+  a.split_ws = (float*)dev_scratch; a.split_ws_bytes = dev_scratch ? scratch_bytes : 0;
   HIP_TRY(launch_attention(a, (hipStream_t)stream));
   return HERO_OK;
+}
+
+int hero_attention(const void* dev_q, const void* dev_k, const void* dev_vt, int64_t ld_vt, void* dev_o,
+                   int32_t r, int32_t n_keys, int32_t n_heads, int32_t head_dim, void* stream) {
+  return hero_attention_scratch(dev_q, dev_k, dev_vt, ld_vt, dev_o, r, n_keys, n_heads, head_dim, nullptr, 0, stream);
 }
 
 int hero_axpy_features(void* dev_x, int32_t x_dtype, const void* s_cur, const void* s_prev, float alpha,

@@ -105,6 +105,8 @@ struct AttnArgs {
   bf16_t* o;            // [r, n_heads*head_dim]
   int32_t r, n_keys, n_heads, head_dim;
   float q_scale;        // scores are exp2(q_scale * q.k): log2(e)/sqrt(head_dim), or 1 if folded into Q
+  float* split_ws;      // optional device scratch for the partial results of key-split query blocks (nullptr: never split)
+  size_t split_ws_bytes;
 };
 
 hipError_t launch_attention(const AttnArgs& a, hipStream_t st);

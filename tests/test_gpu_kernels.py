@@ -157,7 +157,23 @@ def vt_padded(v, ld):
     (70, 272, 4, 32, "huge"),
 ])
 def test_attention(r, n_keys, heads, hd, case):
-    say(f"attention r={r} n_keys={n_keys} heads={heads} hd={hd} {case}")
+    run_attention(r, n_keys, heads, hd, case, scratch_mib=0)
+
+
+# query blocks cut along the keys (their partial sums pass through scratch): every block is cut here
+# because the grid is far smaller than the chip; n_keys = 4133 has 64 whole key tiles and a ragged
+# tail, so ranges of 16 tiles; 3000 keys: ranges of 23 / 23 tiles; 1 MiB of scratch: fewer ranges
+@pytest.mark.parametrize("r,n_keys,heads,hd,case,scratch_mib", [
+    (600, 4133, 4, 64, "plain", 64), (600, 4133, 4, 64, "peaky", 64), (600, 4133, 4, 64, "huge", 64),
+    (600, 4133, 4, 64, "allneg", 64), (600, 4133, 4, 64, "onequery", 64), (257, 3000, 2, 64, "plain", 64),
+    (600, 4133, 4, 64, "plain", 3), (600, 4133, 4, 64, "plain", 1), (300, 2048, 3, 32, "plain", 64),
+])
+def test_attention_with_key_split(r, n_keys, heads, hd, case, scratch_mib):
+    run_attention(r, n_keys, heads, hd, case, scratch_mib)
+
+
+def run_attention(r, n_keys, heads, hd, case, scratch_mib):
+    say(f"attention r={r} n_keys={n_keys} heads={heads} hd={hd} {case} scratch={scratch_mib} MiB")
     d = heads * hd
     q, k, v = rnd(20, r, d), rnd(21, n_keys, d), rnd(22, n_keys, d)
     if case == "peaky":
@@ -173,7 +189,9 @@ def test_attention(r, n_keys, heads, hd, case):
         q[77] = round_to_bf16(q[77] * 200)
     ld = (n_keys + 63) // 64 * 64
     o = torch.full((r + 1, d), 3.0, dtype=torch.bfloat16, device="cuda")
-    B.hero_attention(to_dev_bf16(q), to_dev_bf16(k), to_dev_bf16(vt_padded(v, ld)), o, n_keys, heads, hd)
+    scratch = (torch.full((scratch_mib << 18,), float("nan"), dtype=torch.float32, device="cuda")
+               if scratch_mib else None)
+    B.hero_attention(to_dev_bf16(q), to_dev_bf16(k), to_dev_bf16(vt_padded(v, ld)), o, n_keys, heads, hd, scratch)
     torch.cuda.synchronize()
     want = O.attention(q.astype(np.float64), k.astype(np.float64), v.astype(np.float64), heads)
     assert_close(to_host_f64(o[:r]), want, "attention")
