@@ -345,7 +345,8 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_hd64_kernel(AttnArgs a, 
   u32x4_t (&sK)[3][TILE] = skv[0];
   u32x4_t (&sV)[3][TILE] = skv[1];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform: lives in a scalar register
   const int lr = lane & 31, lh = lane >> 5;
   const int q0 = qb * (NW * 64) + wave * 64;
 
@@ -404,13 +405,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_hd64_kernel(AttnArgs a, 
     v_fo[s] = lr * 8 + ((2 * s + lh) ^ ((lr >> 1) & 7));         // index 2*jb + t; + cb*256
   }
 
-  floatx16_t o[2][2];              // [cb][ig]
-#pragma unroll
-  for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-    for (int ig = 0; ig < 2; ++ig)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) o[cb][ig][e] = 0.f;
+  floatx16_t o[2][2];              // [cb][ig]; cleared after the prologue, which does not touch it
   float la[2] = {0.f, 0.f}, lb[2] = {0.f, 0.f};   // two partial row sums per query group
 
   floatx16_t s0[2], s1[2];         // scores of the even / odd 32-key block, [ig]
@@ -498,7 +493,14 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_hd64_kernel(AttnArgs a, 
     __builtin_amdgcn_sched_barrier(0);
     read_k(1, 0); read_v(0, 0);
     __builtin_amdgcn_sched_barrier(0);
-
+  }
+#pragma unroll
+  for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+    for (int ig = 0; ig < 2; ++ig)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) o[cb][ig][e] = 0.f;
+  if (ntf > 0) {
     // Iteration `tile` (buffer index P = tile % 3): on entry the fragments hold K tile+1 block 0
     // and V^T tile block 0, s1 the scores of block 2*tile+1, p0 the probabilities of block 2*tile.
     // K tile t lives in sK[t % 3], V^T tile t in sV[t % 3]; the loads issued here fill the buffers
@@ -586,6 +588,11 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_hd64_kernel(AttnArgs a, 
   __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): no LDS fill of this wave is still in flight
 
   // ---- row sums ----
+  // (the lane index is taken from the hardware again here: every VGPR is in use inside the loop, and a
+  //  value that is only needed after it would be parked in scratch memory and fetched back)
+  int lane_after;
+  asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(lane_after));
+  const int tid_after = wave * 64 + lane_after;
   float l[2];
 #pragma unroll
   for (int ig = 0; ig < 2; ++ig) {
@@ -602,10 +609,10 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_hd64_kernel(AttnArgs a, 
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           floatx4_t v = {o[cb][ig][4 * q], o[cb][ig][4 * q + 1], o[cb][ig][4 * q + 2], o[cb][ig][4 * q + 3]};
-          *reinterpret_cast<floatx4_t*>(part + (((cb * 2 + ig) * 4 + q) * 256 + tid) * 4) = v;
+          *reinterpret_cast<floatx4_t*>(part + (((cb * 2 + ig) * 4 + q) * 256 + tid_after) * 4) = v;
         }
-    part[64 * 256 + tid] = l[0];
-    part[65 * 256 + tid] = l[1];
+    part[64 * 256 + tid_after] = l[0];
+    part[65 * 256 + tid_after] = l[1];
     return;
   }
   // were the scores inside the range of the reference-free form?
@@ -614,7 +621,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_hd64_kernel(AttnArgs a, 
     attention_general<HD, NW>(a, head, q0, a.q_scale, &sK[0][0], &sV[0][0]);
     return;
   }
-  attention_finish<NW>(a, head, q0, wave, lane, o, l, reinterpret_cast<char*>(&skv[0][0][0]));
+  attention_finish<NW>(a, head, q0, wave, lane_after, o, l, reinterpret_cast<char*>(&skv[0][0][0]));
 }
 
 // Adds up the key ranges of a split query block (one workgroup per block, same thread -> element
