@@ -498,13 +498,14 @@ __global__ __launch_bounds__(512) void gemm256_kernel(GemmArgs g, int tiles_m, i
       // the same holds for every wave: stage t is readable and the other slot is free.
       asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
       __builtin_amdgcn_sched_barrier(0);
-      const bool more = t + 1 < stage_end;
 #pragma unroll
       for (int sl = 0; sl < 4; ++sl) {
         // MFMAs of slice sl-1 (set (sl+1)&1) while the fragments of slice sl arrive in set sl&1
 #pragma unroll
         for (int x = 0; x < 8; ++x) {
-          if (more && sl == 0) fill_one(S ^ 1, t + 1, x);
+          // (after the last stage the same stage is fetched once more into the idle slot: cheaper than
+          //  eight branches per stage, and in bounds)
+          if (sl == 0) fill_one(S ^ 1, min(t + 1, stage_end - 1), x);
           if (x < 6) read_frag(sl & 1, S, sl, x);
           mma_one((sl + 1) & 1, x);
           __builtin_amdgcn_sched_barrier(0);
@@ -787,9 +788,11 @@ hipError_t launch_gemm256(const GemmArgs& g, hipStream_t st) {
   int n_tiles = tiles_m * tiles_n;
   int per_xcd = (n_tiles + 7) / 8;
   const int slots = per_xcd * 8;
-  // operand panels of a long-k problem are several MB each: shorter groups of row tiles keep
-  // the set that is live in an XCD's L2 small enough
-  const int group_m = g.k >= 8192 ? 4 : 8;
+  // Row tiles walked together by an XCD.  Operand panels of a long-k problem are several MB each,
+  // and a problem with few row tiles gives each XCD only a few groups: both do better with short
+  // groups (in-session A/B at the 5B shapes: QKV of 4485 rows 4 % faster with 4, the 17776-row
+  // problems with k = 3072 0.5 % faster with 8, 16 is 1-7 % slower everywhere).
+  const int group_m = (g.k >= 8192 || tiles_m <= 24) ? 4 : 8;
   // The chip runs 256 workgroups at a time, so the last round of tiles may leave most of it
   // idle.  Cutting those n_rem tiles into s k-chunks makes the round take ceil(n_rem*s/256)/s of
   // a tile's time, and costs a fix-up pass that moves n_rem*s blocks of 256 KB twice (about

@@ -220,6 +220,7 @@ static hipError_t gather_ln_dispatch(const void* x, const bf16_t* add, const int
   if (iters <= 1) LAUNCH(1);
   else if (iters <= 2) LAUNCH(2);
   else if (iters <= 4) LAUNCH(4);
+  else if (iters <= 6) LAUNCH(6);
   else if (iters <= 8) LAUNCH(8);
   else LAUNCH(16);
 #undef LAUNCH
