@@ -73,6 +73,12 @@ def test_cache_bytes(lib):
     assert want <= cb <= want + 256 * 200 + cfg.n_video * 4
     assert wb >= 3 * s + n * cfg.ffn_dim * 2
     assert cb + wb < 40e9          # far below one GPU's 288 GB
+    # rotary positions add a (cos, sin) table: one float pair per video token and channel pair
+    cb_rope, _ = B.hero_cache_bytes(B.make_config(cfg.with_(block_flags=4)))
+    table = cfg.n_video * (cfg.head_dim // 2) * 8
+    assert table <= cb_rope - cb <= table + 256
+    # adaLN and q/k normalisation need no cache memory of their own
+    assert B.hero_cache_bytes(B.make_config(cfg.with_(block_flags=3)))[0] == cb
 
 
 def test_invalid_configs_are_rejected(lib):
