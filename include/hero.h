@@ -183,7 +183,9 @@ int hero_cache_state(hero_cache_t c, int32_t* n_full, int32_t* last_full_step);
  * HERO_PROF_EXTRAP covers both the per-layer update and hero_step's one-pass update of the
  * whole deep stack; HERO_PROF_DEEPSUM is the once-per-generation summation behind the latter.
  * A full layer of a large problem adds its features to x inside the FFN2 kernel: it then has
- * no HERO_PROF_RESID launch and the time is part of HERO_PROF_GEMM_FF2.
+ * no HERO_PROF_RESID launch and the time is part of HERO_PROF_GEMM_FF2.  A cached hero_step of a
+ * large problem does the same for the refreshed rows and adds the features of all other rows,
+ * of all shallow layers, in its one pass at the end of the step (HERO_PROF_EXTRAP).
  * The three output arrays have 2 * HERO_PROF_KINDS entries (any may be NULL). */
 enum {
   HERO_PROF_SELECT = 0, HERO_PROF_LN = 1, HERO_PROF_GEMM_QKV = 2, HERO_PROF_ATTN = 3,

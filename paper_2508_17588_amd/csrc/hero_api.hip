@@ -341,7 +341,9 @@ int sum_feature_arrays(hero_cache_t c, const std::vector<const bf16_t*>& src, fl
 // for a layer that has only one generation, which then contributes no difference).
 // The sums are cached per state of the deep layers' fill counts and recomputed when it changes;
 // the current sum of one generation serves as the previous sum of the next.
-int apply_deep_stack(hero_cache_t c, void* x, int k, hipStream_t st) {
+// Makes the fp32 sums over the deep layers current (recomputing what a re-fill made stale);
+// *cur / *prev: which of the two arrays holds the sum of S_cur / of S_prev (-1: no previous generation).
+int ensure_deep_sums(hero_cache_t c, hipStream_t st, int* cur_out, int* prev_out) {
   const hero_config& cfg = c->cfg;
   std::vector<int> fills;
   bool any_prev = false;
@@ -376,12 +378,73 @@ int apply_deep_stack(hero_cache_t c, void* x, int k, hipStream_t st) {
     if ((rc = sum_feature_arrays(c, src, c->t[prev], st)) != HERO_OK) return rc;
     c->t_key[prev] = fills; c->t_is_prev[prev] = true;
   }
+  *cur_out = cur;
+  *prev_out = any_prev ? prev : -1;
+  return HERO_OK;
+}
+
+int apply_deep_stack(hero_cache_t c, void* x, int k, hipStream_t st) {
+  const hero_config& cfg = c->cfg;
+  int cur, prev;
+  int rc = ensure_deep_sums(c, st, &cur, &prev);
+  if (rc) return rc;
   const bool x_fp32 = cfg.resid_dtype == HERO_DTYPE_FP32;
   const int64_t n_elems = c->lay.n_tokens * cfg.hidden;
   const float alpha = (float)k / (float)cfg.interval;
-  const double bytes = (double)n_elems * ((x_fp32 ? 8.0 : 4.0) + (any_prev ? 8.0 : 4.0));
+  const double bytes = (double)n_elems * ((x_fp32 ? 8.0 : 4.0) + (prev >= 0 ? 8.0 : 4.0));
   PROF_LAUNCH(c, HERO_PROF_EXTRAP, bytes, st,
-              launch_apply_sums(x, x_fp32, c->t[cur], any_prev ? c->t[prev] : nullptr, alpha, n_elems, st));
+              launch_apply_sums(x, x_fp32, c->t[cur], prev >= 0 ? c->t[prev] : nullptr, alpha, n_elems, st));
+  return HERO_OK;
+}
+
+// Refresh of one shallow layer inside a cached step whose residual adds are deferred to the end
+// of the step: only the refreshed rows of x are updated here (by the FFN2 epilogue).
+int refresh_layer_deferred(hero_cache_t c, int layer, void* x, const int32_t* idx, int n_sel, hipStream_t st) {
+  LayerState& ls = c->layers[layer];
+  if (!ls.has_weights) return fail(HERO_ERR_STATE, "layer %d has no weights", layer);
+  if (ls.fills == 0) return fail(HERO_ERR_STATE, "layer %d refreshed before a full step filled its cache", layer);
+  if (n_sel <= 0) return HERO_OK;
+  bool fused = false;
+  int rc = run_block_rows(c, ls, x, idx, n_sel, ls.k, ls.vt, ls.s_cur, st, &fused);
+  if (rc) return rc;
+  if (!fused) return fail(HERO_ERR_STATE, "internal: the FFN2 kernel did not take the residual update");
+  return HERO_OK;
+}
+
+// Whether a cached step with n_sel refreshed rows can defer its residual adds: the FFN2 kernel
+// must be the one that updates x for its rows.
+bool can_defer_residual(hero_cache_t c, int n_sel) {
+  const hero_config& cfg = c->cfg;
+  if (cfg.n_shallow < 1 || cfg.n_shallow > 48) return false;
+  if (n_sel == 0) return true;
+  GemmArgs g;
+  memset(&g, 0, sizeof(g));
+  g.m = n_sel; g.n = cfg.hidden; g.k = cfg.ffn_dim; g.epilogue = EPI_SCATTER_ADD;
+  return gemm_can_update_x(g);
+}
+
+// The deferred adds of a cached step (see end_of_cached_step_kernel), incl. the deep stack when it
+// has fp32 sums (two or more deep layers).
+int end_of_cached_step(hero_cache_t c, void* x, int k, int n_sel, hipStream_t st) {
+  const hero_config& cfg = c->cfg;
+  const int n_deep = cfg.n_layers - cfg.n_shallow;
+  int cur = -1, prev = -1;
+  if (n_deep >= 2) {
+    int rc = ensure_deep_sums(c, st, &cur, &prev);
+    if (rc) return rc;
+  }
+  FeatureList fl;
+  fl.n = cfg.n_shallow;
+  for (int l = 0; l < cfg.n_shallow; ++l) fl.p[l] = c->layers[l].s_cur;
+  const bool x_fp32 = cfg.resid_dtype == HERO_DTYPE_FP32;
+  const int64_t n_elems = c->lay.n_tokens * cfg.hidden;
+  const float alpha = (float)k / (float)cfg.interval;
+  const double bytes = (double)n_elems * (x_fp32 ? 8.0 : 4.0) +
+                       (double)(c->lay.n_tokens - n_sel) * cfg.hidden * 2.0 * cfg.n_shallow +
+                       (cur >= 0 ? (double)n_elems * (prev >= 0 ? 8.0 : 4.0) : 0.0);
+  PROF_LAUNCH(c, HERO_PROF_EXTRAP, bytes, st,
+              launch_end_of_cached_step(x, x_fp32, fl, c->ages, cfg.n_text, cfg.hidden, cur >= 0 ? c->t[cur] : nullptr,
+                                        prev >= 0 ? c->t[prev] : nullptr, alpha, n_elems, st));
   return HERO_OK;
 }
 
@@ -617,9 +680,20 @@ int hero_step(hero_cache_t c, void* dev_x, int32_t step, void* stream) {
   int32_t n_sel = 0;
   if ((rc = hero_select(c, step, c->idx, &n_sel, stream)) != HERO_OK) return rc;
   c->last_n_sel = n_sel;
+  const int n_deep = cfg.n_layers - cfg.n_shallow;
+  if (can_defer_residual(c, n_sel)) {
+    // Only the refreshed rows of x are needed between the shallow layers of a cached step, so the
+    // residual adds of all other rows wait for one pass at the end of the step (together with the
+    // deep stack): one launch instead of one per shallow layer.
+    for (int l = 0; l < cfg.n_shallow; ++l)
+      if ((rc = refresh_layer_deferred(c, l, dev_x, c->idx, n_sel, (hipStream_t)stream)) != HERO_OK) return rc;
+    if ((rc = end_of_cached_step(c, dev_x, k, n_sel, (hipStream_t)stream)) != HERO_OK) return rc;
+    if (n_deep == 1) return hero_extrapolate_layer(c, cfg.n_shallow, dev_x, k, stream);
+    return HERO_OK;
+  }
   for (int l = 0; l < cfg.n_shallow; ++l)
     if ((rc = hero_refresh_layer(c, l, dev_x, c->idx, n_sel, stream)) != HERO_OK) return rc;
-  if (cfg.n_layers - cfg.n_shallow >= 2) return apply_deep_stack(c, dev_x, k, (hipStream_t)stream);
+  if (n_deep >= 2) return apply_deep_stack(c, dev_x, k, (hipStream_t)stream);
   for (int l = cfg.n_shallow; l < cfg.n_layers; ++l)
     if ((rc = hero_extrapolate_layer(c, l, dev_x, k, stream)) != HERO_OK) return rc;
   return HERO_OK;

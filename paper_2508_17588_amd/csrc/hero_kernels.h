@@ -56,6 +56,11 @@ struct FeatureList {
 hipError_t launch_sum_features(const FeatureList& fl, float* t, bool accumulate, int64_t n_elems, hipStream_t st);
 hipError_t launch_apply_sums(void* x, bool x_fp32, const float* t_cur, const float* t_prev, float alpha,
                              int64_t n_elems, hipStream_t st);
+// rows whose age is not 0 (and text rows): x += sum of the listed features; all rows: x += the deep-stack term
+// from t_cur / t_prev (both optional)
+hipError_t launch_end_of_cached_step(void* x, bool x_fp32, const FeatureList& shallow, const int32_t* ages, int n_text,
+                                     int hidden, const float* t_cur, const float* t_prev, float alpha,
+                                     int64_t n_elems, hipStream_t st);
 
 // GEMM epilogues: what happens to act(A W^T + bias)
 enum GemmEpilogue {

@@ -355,6 +355,68 @@ hipError_t launch_apply_sums(void* x, bool x_fp32, const float* t_cur, const flo
   return hipGetLastError();
 }
 
+// End of a cached step in one pass (Alg. 1's residual adds of the whole step, deferred):
+//   rows not refreshed in this step:  x += sum over the shallow layers of their cached S
+//   every row:                        x += (1 + alpha) T_cur - alpha T_prev   (the deep stack, if any)
+// Refreshed rows got their shallow features added layer by layer by the FFN2 epilogue (the next
+// layer's refresh reads them); a row is refreshed iff it is a video row whose age the selection
+// of this step has just set to 0.
+template <typename XT>
+__global__ __launch_bounds__(256) void end_of_cached_step_kernel(
+    XT* __restrict__ x, FeatureList shallow, const int32_t* __restrict__ ages, int n_text, int hidden,
+    const float* __restrict__ t_cur, const float* __restrict__ t_prev, float alpha, int64_t n_chunks) {
+  int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= n_chunks) return;
+  const int row = (int)((c * 8) / hidden);
+  const bool refreshed = row >= n_text && ages[row - n_text] == 0;
+  float xv[8], acc[8];
+  ResidIO<XT>::load8(x + c * 8, xv);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+  if (!refreshed) {
+    for (int l = 0; l < shallow.n; ++l) {
+      float v[8];
+      load8_stream(shallow.p[l] + c * 8, v);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[j] += v[j];
+    }
+  }
+  if (t_cur != nullptr) {
+    float cv[8];
+    ResidIO<float>::load8(t_cur + c * 8, cv);
+    if (t_prev != nullptr) {
+      float pv[8];
+      ResidIO<float>::load8(t_prev + c * 8, pv);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[j] += cv[j] + (cv[j] - pv[j]) * alpha;
+    } else {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[j] += cv[j];
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < 8; ++j) xv[j] += acc[j];
+  ResidIO<XT>::store8(x + c * 8, xv);
+}
+
+hipError_t launch_end_of_cached_step(void* x, bool x_fp32, const FeatureList& shallow, const int32_t* ages, int n_text,
+                                     int hidden, const float* t_cur, const float* t_prev, float alpha,
+                                     int64_t n_elems, hipStream_t st) {
+  int64_t n_chunks = n_elems / 8;
+  if (n_chunks <= 0) return hipSuccess;
+  if (hidden % 8 != 0) return hipErrorInvalidValue;
+  int64_t blocks = (n_chunks + 255) / 256;
+  if (blocks > (1 << 30)) return hipErrorInvalidValue;
+  dim3 grid((unsigned)blocks), block(256);
+  if (x_fp32)
+    hipLaunchKernelGGL(end_of_cached_step_kernel<float>, grid, block, 0, st, static_cast<float*>(x), shallow, ages, n_text,
+                       hidden, t_cur, t_prev, alpha, n_chunks);
+  else
+    hipLaunchKernelGGL(end_of_cached_step_kernel<bf16_t>, grid, block, 0, st, static_cast<bf16_t*>(x), shallow, ages,
+                       n_text, hidden, t_cur, t_prev, alpha, n_chunks);
+  return hipGetLastError();
+}
+
 // ---------------------------------------------------------------------------------
 // Stability analysis (Sec. 3.2): sums of D and D^2 over all elements, where
 // D = F_{t+1} - 2 F_t + F_{t-1} is the second-order temporal difference of a layer's feature.

@@ -215,3 +215,42 @@ def test_cvx5b_long_video_refresh_and_extrapolation():
     want = x2.astype(np.float64) + s_cur + (s_cur - s_prev) * 0.5      # Eq. 5 with k/M = 1/2
     np.testing.assert_allclose(to_host_f64(xd), want, rtol=0, atol=4e-6)
     cache.close()
+
+
+@pytest.mark.parametrize("n_layers,n_shallow", [(4, 2), (3, 2), (2, 2)])
+def test_cached_step_with_deferred_residual_adds_matches_the_per_layer_calls(n_layers, n_shallow):
+    """At this size hero_step defers the residual adds of a cached step: refreshed rows are updated
+    by the FFN2 kernel layer by layer, all other rows once at the end of the step together with the
+    deep stack.  It must agree, up to the order of fp32 additions, with the per-layer entry points
+    (each of which is checked against the oracle elsewhere), and leave the same caches."""
+    cfg = get_config("cvx5b_42l").with_(n_layers=n_layers, n_shallow=n_shallow, interval=2)
+    say(f"cvx5b shape, {n_layers} layers ({n_shallow} shallow): hero_step vs per-layer calls over 4 steps")
+    ws = [make_layer_weights(cfg, l, seed=0) for l in range(n_layers)]
+    a, b = B.HeroCache(B.make_config(cfg)), B.HeroCache(B.make_config(cfg))
+    upload_weights(a, cfg, ws)
+    upload_weights(b, cfg, ws)
+    n_sel = B.hero_num_selected(a.cfg)
+    idx = torch.empty(n_sel, dtype=torch.int32, device="cuda")
+    x0 = make_tokens(cfg, seed=1)
+    for step in range(4):
+        xin = torch.from_numpy(x0 if step == 0 else perturb_tokens(x0, seed=10 + step, std=0.1)).cuda()
+        xa, xb = xin.clone(), xin.clone()
+        a.hero_step(xa, step)
+        if step % 2 == 0:
+            for l in range(n_layers):
+                b.hero_full_layer(l, xb)
+            b.hero_reset_ages()
+        else:
+            assert b.hero_select(step, idx) == n_sel
+            for l in range(n_shallow):
+                b.hero_refresh_layer(l, xb, idx, n_sel)
+            for l in range(n_shallow, n_layers):
+                b.hero_extrapolate_layer(l, xb, 1)
+        torch.cuda.synchronize()
+        diff = float((xa - xb).abs().max())
+        assert diff <= 5e-5, f"step {step}: x differs by {diff:.3e}"
+        assert torch.equal(a.hero_cache_view(0, B.VIEW_AGES), b.hero_cache_view(0, B.VIEW_AGES))
+        for l in range(n_layers):
+            assert torch.equal(a.hero_cache_view(l, B.VIEW_S_CUR), b.hero_cache_view(l, B.VIEW_S_CUR)), (step, l)
+    a.close()
+    b.close()
