@@ -806,7 +806,8 @@ hipError_t launch_gemm256(const GemmArgs& g, hipStream_t st) {
   sk.split = 1;
   sk.ws = g.splitk_ws;
   const int n_rem = slots - sk.full_items;
-  if (g.splitk_ws != nullptr && n_rem > 0 && sk.full_items <= 8 * 256) {
+  // (the QKV projection is never cut: its k is the hidden size, too short to pay at the supported sizes)
+  if (g.splitk_ws != nullptr && g.epilogue != EPI_QKV && n_rem > 0 && sk.full_items <= 8 * 256) {
     const int stages = g.k / SBK;
     const int s_max = (int)std::min<size_t>((size_t)std::min(stages / 32, 8),
                                             g.splitk_ws_bytes / ((size_t)n_rem * 262144));
