@@ -349,3 +349,24 @@ def test_stability_scores_from_a_runs_own_caches():
     np.testing.assert_allclose(var_gpu, var_orc, rtol=0.05)
     np.testing.assert_allclose(B.hero_stability_scores(var_gpu), O.stability_scores(var_orc), atol=0.05)
     cache.close()
+
+
+def test_full_layer_with_out_projection_and_ffn2_cut_along_k():
+    """hidden = ffn = 4096 and exactly 2048 tokens: 128 tiles of 256 x 256 in the out-projection and
+    in FFN2, each cut into two k-chunks (scatter and accumulate epilogues through the fix-up kernel,
+    FFN2 also updating x), checked on every element."""
+    cfg = get_config("tiny", n_layers=1, n_shallow=1, hidden=4096, n_heads=64, head_dim=64, ffn_dim=4096,
+                     frames=2, height=30, width=34, n_text=8)
+    assert cfg.n_tokens == 2048
+    say("one full layer, d = ffn = 4096, 2048 tokens")
+    cache, orc = make(cfg, 0.02)
+    x0 = make_tokens(cfg, seed=1)
+    xd = dev_x(x0)
+    cache.hero_full_layer(0, xd)
+    xo = orc.full_layer(0, x0.astype(np.float64))
+    torch.cuda.synchronize()
+    c = orc.caches[0]
+    assert_close(to_host_f64(cache.hero_cache_view(0, B.VIEW_S_CUR)), c.g_attn + c.g_ffn, "S", stored_parts=[c.g_attn])
+    assert_close(to_host_f64(xd) - x0.astype(np.float64), c.g_attn + c.g_ffn, "x increment", stored_parts=[c.g_attn])
+    assert_close(to_host_f64(cache.hero_cache_view(0, B.VIEW_K)), c.k, "K")
+    cache.close()
