@@ -49,9 +49,13 @@ the design notes at the repository root):
     tanh-form GELU and softmax scale 1/sqrt(head_dim).
 
 Parity status: every function here is pinned by tests/test_oracle_*.py against
-closed forms, brute force, library routines or invariants, except the
-sampling rule itself (the paper gives no formula): its invariants are pinned,
-the particular choice among valid selections is this document's.
+closed forms, brute force, library routines, enumerated probabilities or
+invariants.  Parity unpinned (the paper gives no formula; the invariants are
+pinned, the particular choice is this repository's reading): which tokens a
+patch yields under either sampling rule; the normalisation of the stability
+score (min-max, inverted); the composition of the modulated block (where the
+gate sits, which stream a row belongs to, the rotary channel split), whose
+pieces are each pinned against their textbook definitions.
 """
 from __future__ import annotations
 
