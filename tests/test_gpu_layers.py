@@ -122,9 +122,10 @@ def round_x(x64, resid_fp32):
     return np.asarray(x64, np.float32)
 
 
-def test_refresh_all_rows_reproduces_full_forward_and_empty_is_reuse():
-    cfg = get_config("tiny", **MID).with_(n_layers=1, n_shallow=1)
-    say("refresh idx = all rows == full forward; n_sel = 0 == reuse")
+@pytest.mark.parametrize("flags", [0, ALL_BLOCK])
+def test_refresh_all_rows_reproduces_full_forward_and_empty_is_reuse(flags):
+    cfg = get_config("tiny", **MID).with_(n_layers=1, n_shallow=1, block_flags=flags)
+    say(f"refresh idx = all rows (text rows included, random order) == full forward; n_sel = 0 == reuse; block_flags={flags}")
     cache, orc = make(cfg, 0.04)
     x0 = make_tokens(cfg, seed=1)
     x1 = perturb_tokens(x0, seed=2, std=0.5)
@@ -141,7 +142,12 @@ def test_refresh_all_rows_reproduces_full_forward_and_empty_is_reuse():
     xd = dev_x(x1)
     cache.hero_refresh_layer(0, xd, torch.from_numpy(perm).cuda(), len(perm))
     torch.cuda.synchronize()
-    y, g_attn, g_ffn, k, v = O.block_forward(x1.astype(np.float64), orc.w[0], cfg.n_heads, cfg.ln_eps)
+    if flags:
+        ref = O.HeroOracle(cfg, orc.w)             # a fresh oracle: the modulated block's full layer on x1
+        y = ref.full_layer(0, x1.astype(np.float64))
+        g_attn, g_ffn, k, v = ref.caches[0].g_attn, ref.caches[0].g_ffn, ref.caches[0].k, ref.caches[0].v
+    else:
+        y, g_attn, g_ffn, k, v = O.block_forward(x1.astype(np.float64), orc.w[0], cfg.n_heads, cfg.ln_eps)
     assert_close(to_host_f64(xd), y, "refresh(all rows): x")
     assert_close(to_host_f64(cache.hero_cache_view(0, B.VIEW_S_CUR)), g_attn + g_ffn, "refresh(all rows): S")
     assert_close(to_host_f64(cache.hero_cache_view(0, B.VIEW_K)), k, "refresh(all rows): K")
