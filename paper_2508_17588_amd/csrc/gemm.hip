@@ -1,6 +1,10 @@
 // bf16 MFMA GEMM for the refreshed rows: C = act(A W^T + bias), A [M,K], W [N,K] both
 // K-contiguous (QKV projection, out-projection and FFN of Eq. 2 / Eq. 3), fp32 accumulate.
 //
+// Two kernels: problems with fewer than 128 tiles of 256 x 256 use the 128 x 128-tile kernel
+// described here (register-staged loads); larger ones use gemm256_kernel further down (direct
+// global -> LDS loads into a two-slot ring, k-split of a thin last round; described there).
+//
 // Tiling (gfx950, wave64): a workgroup owns a BM x BN tile of C and walks K in steps of 64.
 // Each wave owns a WM x WN sub-tile made of 32x32 blocks computed by
 // v_mfma_f32_32x32x16_bf16 (A fragment: lane holds row lane%32, eight consecutive k
