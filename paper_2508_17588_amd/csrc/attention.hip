@@ -32,13 +32,16 @@
 //    recomputes its output with the general path below.  K/V tiles go global -> LDS directly
 //    (buffer_load ... lds, 16 bytes per lane) into three rotating buffers, one barrier per
 //    64-key tile; K/V fragments are refilled from LDS half a step before they are used.
+//    The chip holds 512 workgroups at a time; the query blocks of the last, partly filled round
+//    are cut into key ranges, each a work item of its own whose unnormalised output and row sums
+//    go to a caller-provided workspace (they simply add, there being no reference point), and a
+//    fix-up kernel adds them, makes the row-sum check on the totals and finishes the block.
 //
 //  * the general path (head_dim 32, and the fallback of the production path): classic online
 //    softmax with a running maximum that is only raised when some query exceeds it by more
 //    than 2^8, one 64-key tile at a time, register-staged double-buffered LDS.
-#include <type_traits>
-
 #include <algorithm>
+#include <type_traits>
 
 #include "hero_device.h"
 #include "hero_kernels.h"
