@@ -162,7 +162,12 @@ int hero_extrapolate_layer(hero_cache_t c, int32_t layer, void* dev_x, int32_t k
  * pass: it keeps T = sum over deep layers of S (fp32, one array per full-step
  * generation, summed once after each full step) and adds
  * (1 + k/M) T_t - (k/M) T_{t+M}.  The result equals calling
- * hero_extrapolate_layer for every deep layer up to fp32 summation order. */
+ * hero_extrapolate_layer for every deep layer up to fp32 summation order.
+ * Likewise, between the shallow layers of a cached step only the refreshed rows
+ * of x are read, so at large shapes hero_step updates those rows layer by layer
+ * and adds the shallow layers' cached features to all other rows once, in the
+ * same final pass; x equals the result of the per-layer calls up to fp32
+ * summation order and the caches are identical. */
 int hero_step(hero_cache_t c, void* dev_x, int32_t step, void* stream);
 
 /* Read-only views into the handle, for tests and tools.  `what`:
