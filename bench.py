@@ -30,6 +30,8 @@ def parse():
     p.add_argument("--workload", default="cvx5b_42l")
     p.add_argument("--block-flags", type=int, default=0,
                    help="1 adaLN modulation + 2 q/k LayerNorm + 4 rotary positions (default 0: the plain block)")
+    p.add_argument("--select-mode", type=int, default=0,
+                   help="0 age-priority selection (default), 1 age-weighted random sampling")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--cpu-sample-rows", type=int, default=4485)
     return p.parse_args()
@@ -111,7 +113,11 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     B.load_library()          # fails loudly when the HIP library has not been built
-    cfg = get_config(args.workload, block_flags=args.block_flags) if args.block_flags else get_config(args.workload)
+    cfg = get_config(args.workload)
+    if args.block_flags:
+        cfg = cfg.with_(block_flags=args.block_flags)
+    if args.select_mode:
+        cfg = cfg.with_(select_mode=args.select_mode)
     torch.cuda.set_device(0)
     gen = torch.Generator(device="cuda")
     gen.manual_seed(0)
@@ -213,7 +219,7 @@ def main():
         "config": {"workload": args.workload, "layers": cfg.n_layers, "shallow_layers": cfg.n_shallow,
                    "interval": cfg.interval, "hidden": cfg.hidden, "heads": cfg.n_heads, "ffn": cfg.ffn_dim,
                    "tokens": cfg.n_tokens, "refreshed_rows": n_sel, "resid": "fp32" if cfg.resid_fp32 else "bf16",
-                   "block_flags": cfg.block_flags},
+                   "block_flags": cfg.block_flags, "select_mode": cfg.select_mode},
         "full_step_ms": round(mean(full_ms), 3) if full_ms else None,
         "cached_step_ms": round(mean(cached_ms), 3) if cached_ms else None,
         "speedup_vs_all_full": round(mean(full_ms) / ms_per_step, 3) if full_ms else None,
