@@ -3,7 +3,8 @@
 //
 // Two kernels: problems with fewer than 128 tiles of 256 x 256 use the 128 x 128-tile kernel
 // described here (register-staged loads); larger ones use gemm256_kernel further down (direct
-// global -> LDS loads into a two-slot ring, k-split of a thin last round; described there).
+// global -> LDS loads into rings of three A slots and two W slots, k-split of a thin last round;
+// described there).
 //
 // Tiling (gfx950, wave64): a workgroup owns a BM x BN tile of C and walks K in steps of 64.
 // Each wave owns a WM x WN sub-tile made of 32x32 blocks computed by
@@ -304,23 +305,29 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_kernel(GemmAr
 
 // ------------------------------------------------------------------------------------------
 // Large problems: 256 x 256 tile, eight waves (two per SIMD) of 128 x 64, K walked in stages of
-// 64 through two LDS slots that are filled by direct global -> LDS loads (16 bytes per lane).
+// 64 through LDS rings (three slots for A, two for W: all 160 KB of a CU) that are filled by
+// direct global -> LDS loads (16 bytes per lane).
 //
 //  * What bounds this kernel is the rate at which a CU's vector cache can keep cache-line
 //    requests in flight, so every request must be a whole 128-byte line: a wave-wide load
 //    fetches eight rows of 128 bytes (eight consecutive lanes per row).
 //  * Two waves per SIMD: a wave whose load waits for the address unit cannot issue MFMAs
 //    meanwhile; with a second wave on the SIMD the matrix pipe keeps running.  Each wave issues
-//    its eight loads of the next stage in the first quarter of the current one, one per MFMA,
-//    so that the slowest of them has most of a stage to arrive before the barrier needs it.
+//    eight loads in the first quarter of a stage, one per MFMA: its W blocks of the next stage
+//    and its A blocks of the stage after that.  The weight panels are shared by every row tile
+//    and mostly hit in the caches, so one stage is enough for them; the activation panels
+//    stream from HBM (few workgroups read each), and the extra stage of distance takes their
+//    misses off the barrier's wait.
 //  * LDS layout of a stage: rows of 128 B whose eight 16-byte chunks are XOR-swizzled with
 //    (row/2)%8 (conflict-free ds_read_b128 fragment reads).  A direct load writes lane l to
 //    byte 16*l of its 1 KB block, i.e. row l/8, chunk slot l%8, so the lane fetches the chunk
 //    that belongs in that slot.
-//  * One barrier per stage.  After the barrier of stage t every wave holds the fragments of
-//    the last k-slice of stage t-1 in registers and has no LDS read outstanding, so the loads
-//    of stage t+1 can overwrite the slot of stage t-1 at once; they have the whole stage
-//    (~2000 cycles) to land.  The fragments of the first slice of stage t are read while the
+//  * One barrier per stage.  Loads complete in issue order, so "all but my four newest" before
+//    the barrier of stage t means A and W of stage t are in LDS.  After that barrier every wave
+//    holds the fragments of the last k-slice of stage t-1 in registers and has no LDS read
+//    outstanding, so the new loads can overwrite the slots of stage t-1 at once (W of t+1 into
+//    the other W slot, A of t+2 into the third A slot); they have one and two whole stages
+//    (~2000 cycles each) to land.  The fragments of the first slice of stage t are read while the
 //    MFMAs of that last slice run, which hides the LDS latency behind the barrier.
 //  * The waves accumulate C^T blocks (operands swapped), so a lane owns one row m and four
 //    consecutive columns n per accumulator quad.  The epilogue adds the bias, applies the
@@ -331,14 +338,16 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_kernel(GemmAr
 //    stages fp32 in two halves and rounds once after adding the cached row.
 // ------------------------------------------------------------------------------------------
 constexpr int SBK = 64;                       // k elements per stage: one 128-byte line per row
-constexpr int RING = 2;                       // LDS slots
+constexpr int RING_B = 2;                     // W slots: its fills run one stage ahead
 constexpr int STAGE_BYTES = 256 * SBK * 2;    // one operand, one stage: 32 KB
-constexpr int RING_B_OFF = RING * STAGE_BYTES;               // W ring starts after the A ring
+constexpr int RING_A = 3;                     // A slots: its fills run two stages ahead
+constexpr int RING_B_OFF = RING_A * STAGE_BYTES;   // the W ring starts after the A ring
 constexpr int CST = 136;                      // bf16 staging: bytes per 64-column row (+8 pad)
 constexpr int CSTT = 264;                     // bf16 staging of a transposed sub-tile: 128 columns (+8 pad)
 constexpr int CST32 = 264;                    // fp32 staging: bytes per 64-column row (+8 pad)
 constexpr int STAGE_REGION = 128 * CST;       // per-wave staging region (17408 B)
-constexpr int GEMM256_LDS = 8 * STAGE_REGION > 2 * RING * STAGE_BYTES ? 8 * STAGE_REGION : 2 * RING * STAGE_BYTES;
+constexpr int RING_BYTES = (RING_A + RING_B) * STAGE_BYTES;   // 160 KB
+constexpr int GEMM256_LDS = 8 * STAGE_REGION > RING_BYTES ? 8 * STAGE_REGION : RING_BYTES;
 static_assert(64 * CST32 <= STAGE_REGION && 64 * CSTT <= STAGE_REGION, "half-tile / transposed tile must fit the staging region");
 
 // buffer resource words: base address, no stride, byte count, raw 32-bit data format
@@ -435,10 +444,11 @@ __global__ __launch_bounds__(512) void gemm256_kernel(GemmArgs g, int tiles_m, i
   const uint32_t fillA = lds0 + wave * 1024, fillB = lds0 + RING_B_OFF + wave * 1024;
   const int n_stages = g.k / SBK;
   const int stage_begin = chunk * n_stages / n_chunks, stage_end = (chunk + 1) * n_stages / n_chunks;
-  auto fill_one = [&](int slot, int stage, int q) {
-    const uint32_t koff = (uint32_t)stage * (SBK * 2);
-    if (q < 4) lds_fill(rsA, fillA + (uint32_t)slot * STAGE_BYTES + q * 8192, voffA[q], koff);
-    else lds_fill(rsB, fillB + (uint32_t)slot * STAGE_BYTES + (q - 4) * 8192, voffB[q - 4], koff);
+  auto fill_a = [&](int slot, int stage, int q) {
+    lds_fill(rsA, fillA + (uint32_t)slot * STAGE_BYTES + q * 8192, voffA[q], (uint32_t)stage * (SBK * 2));
+  };
+  auto fill_b = [&](int slot, int stage, int q) {
+    lds_fill(rsB, fillB + (uint32_t)slot * STAGE_BYTES + q * 8192, voffB[q], (uint32_t)stage * (SBK * 2));
   };
 
   // ---- fragment reads: row R, k-chunk c of a stage sits at R*128 + (c ^ ((R/2)%8))*16 ----
@@ -480,14 +490,14 @@ __global__ __launch_bounds__(512) void gemm256_kernel(GemmArgs g, int tiles_m, i
       if (i < 2) fb[1][i] = *reinterpret_cast<bf16x8_t*>(&z);
     }
     // order in which the 6 fragments of a slice are read (the MFMAs use them in the same order)
-    auto read_frag = [&](int set, int slot, int ks, int q) {
+    auto read_frag = [&](int set, int slot_a, int slot_b, int ks, int q) {
       switch (q) {
-        case 0: fa[set][0] = frag(fa_ks[ks], slot, 0); break;
-        case 1: fb[set][0] = frag(fb_ks[ks], slot, 0); break;
-        case 2: fb[set][1] = frag(fb_ks[ks], slot, 1); break;
-        case 3: fa[set][1] = frag(fa_ks[ks], slot, 1); break;
-        case 4: fa[set][2] = frag(fa_ks[ks], slot, 2); break;
-        default: fa[set][3] = frag(fa_ks[ks], slot, 3); break;
+        case 0: fa[set][0] = frag(fa_ks[ks], slot_a, 0); break;
+        case 1: fb[set][0] = frag(fb_ks[ks], slot_b, 0); break;
+        case 2: fb[set][1] = frag(fb_ks[ks], slot_b, 1); break;
+        case 3: fa[set][1] = frag(fa_ks[ks], slot_a, 1); break;
+        case 4: fa[set][2] = frag(fa_ks[ks], slot_a, 2); break;
+        default: fa[set][3] = frag(fa_ks[ks], slot_a, 3); break;
       }
     };
     auto mma_one = [&](int set, int x) {
@@ -495,12 +505,13 @@ __global__ __launch_bounds__(512) void gemm256_kernel(GemmArgs g, int tiles_m, i
       if (NATURAL) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0);
       else acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][j], fa[set][i], acc[i][j], 0, 0, 0);
     };
-    // one stage: slot S holds stage t
-    auto stage = [&](auto SLOT, int t) {
-      constexpr int S = decltype(SLOT)::value;
-      // Own fills of stage t landed, own fragment reads of stage t-1 complete; after the barrier
-      // the same holds for every wave: stage t is readable and the other slot is free.
-      asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    // one stage: A slot SA and W slot SB hold stage t
+    auto stage = [&](auto SLOT_A, auto SLOT_B, int t) {
+      constexpr int SA = decltype(SLOT_A)::value, SB = decltype(SLOT_B)::value;
+      // All but the four newest fills (A of stage t+1) have landed: A and W of stage t are in LDS.
+      // Own fragment reads of stage t-1 are complete; after the barrier the same holds for every
+      // wave: stage t is readable, and the slots of stage t-1 are free.
+      asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)\n\ts_barrier" ::: "memory");
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int sl = 0; sl < 4; ++sl) {
@@ -509,18 +520,32 @@ __global__ __launch_bounds__(512) void gemm256_kernel(GemmArgs g, int tiles_m, i
         for (int x = 0; x < 8; ++x) {
           // (after the last stage the same stage is fetched once more into the idle slot: cheaper than
           //  eight branches per stage, and in bounds)
-          if (sl == 0) fill_one(S ^ 1, min(t + 1, stage_end - 1), x);
-          if (x < 6) read_frag(sl & 1, S, sl, x);
+          if (sl == 0) {
+            if (x < 4) fill_b(SB ^ 1, min(t + 1, stage_end - 1), x);
+            else fill_a((SA + 2) % 3, min(t + 2, stage_end - 1), x - 4);
+          }
+          if (x < 6) read_frag(sl & 1, SA, SB, sl, x);
           mma_one((sl + 1) & 1, x);
           __builtin_amdgcn_sched_barrier(0);
         }
       }
     };
 #pragma unroll
-    for (int q = 0; q < 8; ++q) fill_one(0, stage_begin, q);
-    for (int t = stage_begin; t < stage_end; t += 2) {
-      stage(std::integral_constant<int, 0>{}, t);
-      if (t + 1 < stage_end) stage(std::integral_constant<int, 1>{}, t + 1);
+    for (int q = 0; q < 4; ++q) fill_a(0, stage_begin, q);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) fill_b(0, stage_begin, q);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) fill_a(1, min(stage_begin + 1, stage_end - 1), q);
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    using I2 = std::integral_constant<int, 2>;
+    for (int t = stage_begin; t < stage_end; t += 6) {
+      stage(I0{}, I0{}, t);
+      if (t + 1 < stage_end) stage(I1{}, I1{}, t + 1);
+      if (t + 2 < stage_end) stage(I2{}, I0{}, t + 2);
+      if (t + 3 < stage_end) stage(I0{}, I1{}, t + 3);
+      if (t + 4 < stage_end) stage(I1{}, I0{}, t + 4);
+      if (t + 5 < stage_end) stage(I2{}, I1{}, t + 5);
     }
     // last slice of the last stage
 #pragma unroll
