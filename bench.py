@@ -32,6 +32,8 @@ def parse():
                    help="1 adaLN modulation + 2 q/k LayerNorm + 4 rotary positions (default 0: the plain block)")
     p.add_argument("--select-mode", type=int, default=0,
                    help="0 age-priority selection (default), 1 age-weighted random sampling")
+    p.add_argument("--ratio", choices=("10", "25", "50"), default=None,
+                   help="refresh ratio in percent, with the patch shape of the one-block ratio sweep")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--cpu-sample-rows", type=int, default=4485)
     return p.parse_args()
@@ -107,13 +109,15 @@ def main():
         sys.exit(2)
     import torch
     from paper_2508_17588_amd import binding as B
-    from workloads import get_config
+    from workloads import RATIO_SWEEP, get_config
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     B.load_library()          # fails loudly when the HIP library has not been built
     cfg = get_config(args.workload)
+    if args.ratio:
+        cfg = cfg.with_(**RATIO_SWEEP[args.ratio])
     if args.block_flags:
         cfg = cfg.with_(block_flags=args.block_flags)
     if args.select_mode:
