@@ -98,6 +98,9 @@ def test_gather_ln(hidden, x_dtype):
 @pytest.mark.parametrize("m,n,k,act", [
     (1, 128, 64, 0), (300, 384, 128, 0), (64, 128, 512, 1), (257, 512, 128, 1),
     (1000, 1920, 256, 0), (3000, 3072, 256, 0), (3001, 3072 + 64, 192, 1), (4485, 5760, 128, 0),
+    # large-tile kernel with 1, 5 and 7 stages of 64 (its stage loop is unrolled six times, the
+    # activation ring is three slots deep)
+    (4096, 2048, 64, 0), (3000, 3072, 320, 1), (3000, 3072, 448, 0),
 ])
 def test_linear(m, n, k, act):
     say(f"linear m={m} n={n} k={k} act={act}")
