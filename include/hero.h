@@ -109,7 +109,10 @@ const char* hero_last_error(void);
 int hero_num_selected(const hero_config* cfg, int32_t* n_sel_host);
 
 /* Bytes of device memory the handle needs: cache (persistent features, K/V,
- * token ages) and workspace (per-call temporaries). */
+ * token ages) and workspace (per-call temporaries).  HERO_ERR_SHAPE for a configuration
+ * the kernels do not support; among the limits, (tokens + 512) * max(hidden, ffn_dim) * 2
+ * must stay below 2^32 (32-bit operand offsets in the GEMM and attention kernels), e.g.
+ * about 174 000 tokens at ffn_dim 12288. */
 int hero_cache_bytes(const hero_config* cfg, size_t* cache_bytes, size_t* workspace_bytes);
 
 /* Carves the caller's two device buffers (256-byte aligned) into slabs and
@@ -212,7 +215,8 @@ int hero_gather_ln(const void* dev_x, int32_t x_dtype, const void* dev_add_bf16,
                    void* dev_out_bf16, void* stream);
 
 /* C[M,N] = act(A[M,K] W[N,K]^T + bias[N]) in bf16 with fp32 accumulation.
- * act: 0 none, 1 tanh-GELU.  K % 64 == 0, N % 64 == 0. */
+ * act: 0 none, 1 tanh-GELU.  K % 64 == 0, N % 64 == 0.  Operands are addressed with 32-bit byte
+ * offsets: (M + 512) * K * 2 and (N + 512) * K * 2 must stay below 2^32, else HERO_ERR_SHAPE. */
 int hero_linear(const void* dev_a, const void* dev_w, const void* dev_bias, void* dev_c,
                 int32_t m, int32_t n, int32_t k, int32_t act, void* stream);
 
@@ -228,7 +232,9 @@ int hero_linear_scratch(const void* dev_a, const void* dev_w, const void* dev_bi
 
 /* O[r,hidden] = softmax(Q K^T / sqrt(head_dim)) V per head; Q [r,hidden], K [n_keys,hidden],
  * V given transposed as vt [hidden, ld_vt] with ld_vt >= n_keys, ld_vt % 64 == 0 and
- * columns n_keys..ld_vt-1 finite (zero).  (FullAttn of Eq. 2 for refreshed queries, Eq. 3.) */
+ * columns n_keys..ld_vt-1 finite (zero).  (FullAttn of Eq. 2 for refreshed queries, Eq. 3.)
+ * K and V^T are addressed with 32-bit byte offsets: (n_keys + 256) * hidden * 2 and
+ * hidden * ld_vt * 2 must stay below 2^32, else HERO_ERR_SHAPE. */
 int hero_attention(const void* dev_q, const void* dev_k, const void* dev_vt, int64_t ld_vt,
                    void* dev_o, int32_t r, int32_t n_keys, int32_t n_heads, int32_t head_dim,
                    void* stream);

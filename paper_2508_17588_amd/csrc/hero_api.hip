@@ -51,6 +51,18 @@ int tokens_per_patch(float ratio, int size) {
   return (int)v;
 }
 
+// The GEMM and attention kernels address their operands with 32-bit byte offsets; a tile may form
+// offsets for up to 512 rows (GEMM) or 256 keys (attention) past the end of an operand, which the
+// hardware bounds check then discards.  These mirror the launchers' own guards.
+bool gemm_offsets_fit(int64_t m, int64_t n, int64_t k) {
+  const int64_t lim = (int64_t)1 << 32;
+  return (m + 512) * k * 2 < lim && (n + 512) * k * 2 < lim;
+}
+bool attention_offsets_fit(int64_t n_keys, int64_t hidden, int64_t ld_vt) {
+  const int64_t lim = (int64_t)1 << 32;
+  return (n_keys + 256) * hidden * 2 < lim && hidden * ld_vt * 2 < lim;
+}
+
 int check_config(const hero_config* c) {
   if (!c) return fail(HERO_ERR_INVALID_ARG, "config is null");
   if (c->n_layers < 1 || c->n_shallow < 0 || c->n_shallow > c->n_layers || c->interval < 1)
@@ -76,6 +88,14 @@ int check_config(const hero_config* c) {
   if (c->hidden > 8192) return fail(HERO_ERR_SHAPE, "hidden must be <= 8192");
   int64_t n = (int64_t)c->n_text + (int64_t)c->frames * c->height * c->width;
   if (n > (1 << 24)) return fail(HERO_ERR_SHAPE, "more than 2^24 tokens");
+  // every GEMM of the block on all n rows, and attention over n keys
+  const int64_t d = c->hidden, f = c->ffn_dim, n_pad = (n + 63) / 64 * 64;
+  if (!gemm_offsets_fit(n, 3 * d, d) || !gemm_offsets_fit(n, f, d) || !gemm_offsets_fit(n, d, f) ||
+      !attention_offsets_fit(n, d, n_pad))
+    return fail(HERO_ERR_SHAPE,
+                "%lld tokens x max(hidden, ffn_dim) = %lld exceeds the kernels' 32-bit operand offsets: "
+                "(tokens + 512) * max(hidden, ffn_dim) * 2 must stay below 2^32",
+                (long long)n, (long long)(d > f ? d : f));
   return HERO_OK;
 }
 
@@ -778,6 +798,8 @@ int hero_linear_scratch(const void* dev_a, const void* dev_w, const void* dev_bi
   if (m < 0 || n <= 0 || k <= 0) return fail(HERO_ERR_INVALID_ARG, "bad sizes");
   if (k % 64 != 0 || n % 64 != 0) return fail(HERO_ERR_SHAPE, "k and n must be multiples of 64");
   if (act != 0 && act != 1) return fail(HERO_ERR_INVALID_ARG, "act must be 0 or 1");
+  if (!gemm_offsets_fit(m, n, k))
+    return fail(HERO_ERR_SHAPE, "(m + 512) * k * 2 and (n + 512) * k * 2 must stay below 2^32 (32-bit operand offsets)");
   if (dev_scratch != nullptr && (uintptr_t)dev_scratch % 16 != 0) return fail(HERO_ERR_INVALID_ARG, "scratch must be 16-byte aligned");
   GemmArgs g;
   memset(&g, 0, sizeof(g));
@@ -800,6 +822,8 @@ int hero_attention_scratch(const void* dev_q, const void* dev_k, const void* dev
   if (r < 0 || n_keys < 1 || n_heads < 1) return fail(HERO_ERR_INVALID_ARG, "bad sizes");
   if (head_dim != 32 && head_dim != 64) return fail(HERO_ERR_SHAPE, "head_dim must be 32 or 64");
   if (ld_vt % 64 != 0 || ld_vt < n_keys) return fail(HERO_ERR_SHAPE, "ld_vt must be a multiple of 64 and >= n_keys");
+  if (!attention_offsets_fit(n_keys, (int64_t)n_heads * head_dim, ld_vt))
+    return fail(HERO_ERR_SHAPE, "(n_keys + 256) * hidden * 2 and hidden * ld_vt * 2 must stay below 2^32 (32-bit operand offsets)");
   AttnArgs a;
   a.q = (const bf16_t*)dev_q; a.k = (const bf16_t*)dev_k; a.vt = (const bf16_t*)dev_vt; a.ld_vt = ld_vt;
   a.o = (bf16_t*)dev_o; a.r = r; a.n_keys = n_keys; a.n_heads = n_heads; a.head_dim = head_dim;

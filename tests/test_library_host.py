@@ -102,6 +102,16 @@ def test_invalid_configs_are_rejected(lib):
     assert rc_of(hidden=128, n_heads=3) == B.HERO_ERR_SHAPE          # hidden != heads * head_dim
     assert rc_of(ffn_dim=100) == B.HERO_ERR_SHAPE
     assert b"multiple" in lib.hero_last_error()
+    # 32-bit operand offsets: (tokens + 512) * max(hidden, ffn_dim) * 2 < 2^32
+    assert rc_of(frames=1, height=2048, width=2500) == B.HERO_ERR_SHAPE      # 5.1 M tokens x ffn 512
+    assert b"32-bit" in lib.hero_last_error()
+
+    def rc_5b(frames):
+        c = B.make_config(get_config("cvx5b_block", frames=frames))
+        n = ctypes.c_int32(0)
+        return lib.hero_num_selected(ctypes.byref(c), ctypes.byref(n))
+    assert rc_5b(128) == B.HERO_OK                # 173 026 tokens x ffn 12288: 4.265e9 bytes
+    assert rc_5b(134) == B.HERO_ERR_SHAPE         # 181 126 tokens: beyond
     assert lib.hero_num_selected(None, None) == B.HERO_ERR_INVALID_ARG
 
 
@@ -125,6 +135,12 @@ def test_null_and_small_buffers_are_rejected_before_any_gpu_work(lib):
     assert lib.hero_linear_scratch(p, p, p, p, 1, 64, 64, 0, ctypes.c_void_p(260), 1 << 20, None) == B.HERO_ERR_INVALID_ARG
     assert lib.hero_attention(p, p, p, 100, p, 1, 100, 1, 64, None) == B.HERO_ERR_SHAPE
     assert lib.hero_attention(p, p, p, 128, p, 1, 100, 1, 48, None) == B.HERO_ERR_SHAPE
+    # operand sizes beyond the kernels' 32-bit offsets
+    assert lib.hero_linear(p, p, p, p, 699_051, 256, 3072, 0, None) == B.HERO_ERR_SHAPE
+    assert b"2^32" in lib.hero_last_error()
+    assert lib.hero_linear(p, p, p, p, 64, 699_051 // 64 * 64 + 64, 3072, 0, None) == B.HERO_ERR_SHAPE
+    assert lib.hero_attention(p, p, p, 699_136, p, 1, 699_100, 48, 64, None) == B.HERO_ERR_SHAPE
+    assert b"2^32" in lib.hero_last_error()
     assert lib.hero_axpy_features(p, 1, p, None, 0.0, 12, None) == B.HERO_ERR_SHAPE
     assert lib.hero_gather_ln(p, 7, None, None, 1, 64, p, p, 1e-5, p, None) == B.HERO_ERR_INVALID_ARG
 
