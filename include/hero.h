@@ -206,7 +206,9 @@ int hero_profile_begin(hero_cache_t c);
 int hero_profile_begin_kinds(hero_cache_t c, uint32_t kind_mask);
 int hero_profile_end(hero_cache_t c, void* stream, double* ms, int64_t* launches, double* work);
 
-/* ---- building blocks, exposed so each kernel can be checked on its own ------------- */
+/* ---- building blocks, exposed so each kernel can be checked on its own -------------
+ * An empty problem (n_rows, M, r or n_elems of 0) is a no-op whose row buffers (x / out, A / C,
+ * Q / O, x / s_cur) are not touched and may be NULL. */
 
 /* out[i,:] = LayerNorm(x[rows[i],:] (+ add[rows[i],:])) * gain + bias, bf16 out [n_rows, hidden].
  * rows == NULL means rows[i] = i.  add may be NULL.  (Eq. 2's LN on gathered rows.) */

@@ -783,7 +783,8 @@ int hero_profile_end(hero_cache_t c, void* stream, double* ms, int64_t* launches
 int hero_gather_ln(const void* dev_x, int32_t x_dtype, const void* dev_add_bf16, const int32_t* dev_rows,
                    int32_t n_rows, int32_t hidden, const void* gain, const void* bias, float eps,
                    void* dev_out_bf16, void* stream) {
-  if (!dev_x || !gain || !bias || !dev_out_bf16) return fail(HERO_ERR_INVALID_ARG, "null pointer");
+  // (the row buffers of an empty problem are never touched and may be null)
+  if (!gain || !bias || (n_rows > 0 && (!dev_x || !dev_out_bf16))) return fail(HERO_ERR_INVALID_ARG, "null pointer");
   if (x_dtype != HERO_DTYPE_FP32 && x_dtype != HERO_DTYPE_BF16) return fail(HERO_ERR_INVALID_ARG, "bad x_dtype");
   if (n_rows < 0) return fail(HERO_ERR_INVALID_ARG, "n_rows < 0");
   if (hidden < 8 || hidden % 8 != 0 || hidden > 8192) return fail(HERO_ERR_SHAPE, "hidden must be a multiple of 8, <= 8192");
@@ -794,7 +795,7 @@ int hero_gather_ln(const void* dev_x, int32_t x_dtype, const void* dev_add_bf16,
 
 int hero_linear_scratch(const void* dev_a, const void* dev_w, const void* dev_bias, void* dev_c, int32_t m,
                         int32_t n, int32_t k, int32_t act, void* dev_scratch, size_t scratch_bytes, void* stream) {
-  if (!dev_a || !dev_w || !dev_bias || !dev_c) return fail(HERO_ERR_INVALID_ARG, "null pointer");
+  if (!dev_w || !dev_bias || (m > 0 && (!dev_a || !dev_c))) return fail(HERO_ERR_INVALID_ARG, "null pointer");
   if (m < 0 || n <= 0 || k <= 0) return fail(HERO_ERR_INVALID_ARG, "bad sizes");
   if (k % 64 != 0 || n % 64 != 0) return fail(HERO_ERR_SHAPE, "k and n must be multiples of 64");
   if (act != 0 && act != 1) return fail(HERO_ERR_INVALID_ARG, "act must be 0 or 1");
@@ -818,7 +819,7 @@ int hero_linear(const void* dev_a, const void* dev_w, const void* dev_bias, void
 int hero_attention_scratch(const void* dev_q, const void* dev_k, const void* dev_vt, int64_t ld_vt, void* dev_o,
                            int32_t r, int32_t n_keys, int32_t n_heads, int32_t head_dim, void* dev_scratch,
                            size_t scratch_bytes, void* stream) {
-  if (!dev_q || !dev_k || !dev_vt || !dev_o) return fail(HERO_ERR_INVALID_ARG, "null pointer");
+  if (!dev_k || !dev_vt || (r > 0 && (!dev_q || !dev_o))) return fail(HERO_ERR_INVALID_ARG, "null pointer");
   if (r < 0 || n_keys < 1 || n_heads < 1) return fail(HERO_ERR_INVALID_ARG, "bad sizes");
   if (head_dim != 32 && head_dim != 64) return fail(HERO_ERR_SHAPE, "head_dim must be 32 or 64");
   if (ld_vt % 64 != 0 || ld_vt < n_keys) return fail(HERO_ERR_SHAPE, "ld_vt must be a multiple of 64 and >= n_keys");
@@ -841,7 +842,7 @@ int hero_attention(const void* dev_q, const void* dev_k, const void* dev_vt, int
 
 int hero_axpy_features(void* dev_x, int32_t x_dtype, const void* s_cur, const void* s_prev, float alpha,
                        int64_t n_elems, void* stream) {
-  if (!dev_x || !s_cur) return fail(HERO_ERR_INVALID_ARG, "null pointer");
+  if (n_elems > 0 && (!dev_x || !s_cur)) return fail(HERO_ERR_INVALID_ARG, "null pointer");
   if (x_dtype != HERO_DTYPE_FP32 && x_dtype != HERO_DTYPE_BF16) return fail(HERO_ERR_INVALID_ARG, "bad x_dtype");
   if (n_elems < 0 || n_elems % 8 != 0) return fail(HERO_ERR_SHAPE, "n_elems must be a non-negative multiple of 8");
   HIP_TRY(launch_axpy_features(dev_x, x_dtype == HERO_DTYPE_FP32, (const bf16_t*)s_cur, (const bf16_t*)s_prev, alpha,

@@ -141,6 +141,26 @@ def test_linear_with_k_split(m, n, k, act, scratch_mib):
     assert float((c[m:] - 7.0).abs().max()) == 0.0
 
 
+def test_empty_problems_are_no_ops():
+    say("linear with m = 0, attention with r = 0, axpy with no elements")
+    w, b = to_dev_bf16(rnd(16, 128, 64)), to_dev_bf16(rnd(17, 128))
+    rows = torch.zeros(4, 64, dtype=torch.bfloat16, device="cuda")
+    c = torch.full((2, 128), 5.0, dtype=torch.bfloat16, device="cuda")
+    B.hero_linear(rows[:0], w, b, c, 0)
+    scratch = torch.zeros(1 << 18, dtype=torch.float32, device="cuda")
+    B.hero_linear_scratch(rows[:0], w, b, c, scratch, 1)
+    k = to_dev_bf16(rnd(18, 64, 64))
+    vt = to_dev_bf16(rnd(19, 64, 64))
+    o = torch.full((2, 64), 5.0, dtype=torch.bfloat16, device="cuda")
+    B.hero_attention(rows[:0], k, vt, o, 64, 1, 64)
+    B.hero_attention(rows[:0], k, vt, o, 64, 1, 64, scratch)
+    x = torch.full((16,), 5.0, dtype=torch.float32, device="cuda")
+    B.hero_axpy_features(x[:0], c.reshape(-1)[:0], None, 0.0)
+    torch.cuda.synchronize()
+    assert float((c - 5.0).abs().max()) == 0.0 and float((o - 5.0).abs().max()) == 0.0
+    assert float((x - 5.0).abs().max()) == 0.0
+
+
 # ---------------------------------------------------------------- attention
 
 def vt_padded(v, ld):
