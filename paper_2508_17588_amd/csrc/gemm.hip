@@ -40,9 +40,12 @@ constexpr int GROUP_M = 8;       // row-tiles walked together (L2 locality)
 __device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
 
 __device__ __forceinline__ float gelu_tanh(float x) {
-  // x/2 (1 + tanh u) = x / (1 + exp(-2u)),  u = sqrt(2/pi) (x + 0.044715 x^3)
-  float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
-  float e = __builtin_amdgcn_exp2f(-2.0f * 1.4426950408889634f * u);
+  // x/2 (1 + tanh u) = x / (1 + exp(-2u)),  u = sqrt(2/pi) (x + 0.044715 x^3);
+  // -2u log2(e) = x (C1 + C2 x^2) with the constants folded: five plain operations and two
+  // transcendentals per element (the epilogue runs while the matrix pipe idles)
+  constexpr float C1 = -2.302208198144325f;     // -2 log2(e) sqrt(2/pi)
+  constexpr float C2 = -0.1029432395800235f;    // C1 * 0.044715
+  float e = __builtin_amdgcn_exp2f(x * __builtin_fmaf(x * x, C2, C1));
   return x * __builtin_amdgcn_rcpf(1.0f + e);
 }
 
