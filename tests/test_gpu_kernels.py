@@ -119,7 +119,7 @@ def test_linear(m, n, k, act):
 
 @pytest.mark.parametrize("m,n,k,act,scratch_mib", [
     (2040, 4096, 4096, 0, 64),       # 128 tiles, all cut in two
-    (2700, 6144, 6144, 1, 64),       # 264 tiles: 256 whole, 8 cut in three
+    (2700, 6144, 6144, 1, 64),       # 264 tiles: 256 whole, 8 cut in six
     (2700, 6144, 6144, 0, 5),        # scratch for two chunks per tile only
     (2700, 6144, 6144, 0, 1),        # scratch too small to cut anything
     (2700, 6144, 1024, 0, 64),       # k too short to cut
