@@ -141,6 +141,39 @@ def test_linear_with_k_split(m, n, k, act, scratch_mib):
     assert float((c[m:] - 7.0).abs().max()) == 0.0
 
 
+def _random_linear_shapes():
+    """Seeded shapes around the kernels' tile edges: both kernels, ragged m, every n and k granule."""
+    g = np.random.default_rng(2024)
+    shapes = []
+    for _ in range(10):         # small-tile kernel
+        shapes.append((int(g.integers(1, 1500)), 64 * int(g.integers(1, 20)), 64 * int(g.integers(1, 12))))
+    for _ in range(8):          # at least 128 tiles of 256 x 256: large-tile kernel, 1 to 3 rounds
+        tm, tn = int(g.integers(8, 30)), int(g.integers(8, 24))
+        tn = max(tn, -(-128 // tm))
+        shapes.append((256 * tm - int(g.integers(0, 255)), 256 * tn - 64 * int(g.integers(0, 4)), 64 * int(g.integers(1, 40))))
+    return shapes
+
+
+@pytest.mark.parametrize("m,n,k", _random_linear_shapes())
+def test_linear_random_shapes(m, n, k):
+    say(f"linear (random shape) m={m} n={n} k={k}")
+    a = rnd(60, m, k)
+    w = rnd(61, n, k, scale=1.0 / np.sqrt(k))
+    b = rnd(62, n, scale=0.5)
+    want = O.gelu_tanh(O.linear(a.astype(np.float64), w.astype(np.float64), b.astype(np.float64)))
+    ad, wd, bd = to_dev_bf16(a), to_dev_bf16(w), to_dev_bf16(b)
+    scratch = torch.full((64 << 18,), float("nan"), dtype=torch.float32, device="cuda")
+    for use_scratch in (False, True):
+        c = torch.full((m + 1, n), 9.0, dtype=torch.bfloat16, device="cuda")
+        if use_scratch:
+            B.hero_linear_scratch(ad, wd, bd, c, scratch, 1)
+        else:
+            B.hero_linear(ad, wd, bd, c, 1)
+        torch.cuda.synchronize()
+        assert_close(to_host_f64(c[:m]), want, f"linear random shape scratch={use_scratch}")
+        assert float((c[m:] - 9.0).abs().max()) == 0.0
+
+
 def test_empty_problems_are_no_ops():
     say("linear with m = 0, attention with r = 0, axpy with no elements")
     w, b = to_dev_bf16(rnd(16, 128, 64)), to_dev_bf16(rnd(17, 128))
@@ -193,6 +226,20 @@ def test_attention(r, n_keys, heads, hd, case):
 ])
 def test_attention_with_key_split(r, n_keys, heads, hd, case, scratch_mib):
     run_attention(r, n_keys, heads, hd, case, scratch_mib)
+
+
+def _random_attention_shapes():
+    g = np.random.default_rng(77)
+    out = []
+    for i in range(12):
+        hd = 64 if i % 3 else 32
+        out.append((int(g.integers(1, 900)), int(g.integers(1, 5000)), int(g.integers(1, 5)), hd, 64 if i % 2 else 0))
+    return out
+
+
+@pytest.mark.parametrize("r,n_keys,heads,hd,scratch_mib", _random_attention_shapes())
+def test_attention_random_shapes(r, n_keys, heads, hd, scratch_mib):
+    run_attention(r, n_keys, heads, hd, "plain", scratch_mib)
 
 
 def run_attention(r, n_keys, heads, hd, case, scratch_mib):
