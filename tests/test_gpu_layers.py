@@ -264,6 +264,33 @@ def test_reduced_42_layer_schedule():
     run_schedule(cfg, 0.02, cfg.n_steps, check_every_step=False)
 
 
+def _random_configs():
+    """Seeded small configurations: head_dim 32 and 64, odd grids, clipped patches, every schedule shape."""
+    g = np.random.default_rng(4242)
+    out = []
+    for i in range(8):
+        hd = 64 if i % 2 else 32
+        heads = int(g.integers(1, 5)) if hd == 64 else 2 * int(g.integers(1, 3))    # hidden is a multiple of 64
+        layers = int(g.integers(2, 6))
+        out.append(dict(
+            n_layers=layers, n_shallow=int(g.integers(0, layers + 1)), interval=int(g.integers(1, 5)),
+            hidden=heads * hd, n_heads=heads, head_dim=hd, ffn_dim=64 * int(g.integers(1, 9)),
+            frames=int(g.integers(1, 4)), height=int(g.integers(3, 12)), width=int(g.integers(3, 14)),
+            n_text=int(g.integers(0, 40)), patch_h=int(g.integers(1, 4)), patch_w=int(g.integers(1, 4)),
+            ratio=float(g.choice([0.1, 0.25, 0.34, 0.5, 0.8])), select_mode=int(i % 3 == 2),
+            block_flags=int(g.choice([0, 0, ALL_BLOCK])) if hd % 16 == 0 else 0))
+    return out
+
+
+@pytest.mark.parametrize("over", _random_configs(), ids=lambda o: "L{n_layers}K{n_shallow}M{interval}d{hidden}".format(**o))
+def test_random_configurations_through_the_schedule(over):
+    cfg = get_config("tiny", **over)
+    say(f"random configuration {over}")
+    # (weights N(0, 0.03): the two sides keep their own trajectories over the steps, and with 0.05
+    #  five modulated layers over four steps drift to 1.1 x the per-call bound on single elements)
+    run_schedule(cfg, 0.03, 2 * over["interval"] + 2)
+
+
 def test_special_schedules():
     say("K = 0 (every layer extrapolated) and K = L (every layer refreshed)")
     run_schedule(get_config("tiny", n_shallow=0, interval=2), 0.05, 5)
