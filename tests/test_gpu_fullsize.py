@@ -14,7 +14,7 @@ from oracle import hero_oracle as O
 from paper_2508_17588_amd import binding as B
 from workloads import (RATIO_SWEEP, BLOCK_ADALN, BLOCK_QKNORM, BLOCK_ROPE, get_config, make_block_extras,
                        make_layer_weights, make_tokens, perturb_tokens)
-from hero_testlib import assert_close, to_host_f64, upload_weights
+from hero_testlib import assert_close, to_dev_bf16, to_host_f64, upload_weights
 
 pytestmark = pytest.mark.gpu
 
@@ -251,6 +251,58 @@ def test_cached_step_with_deferred_residual_adds_matches_the_per_layer_calls(n_l
         assert diff <= 5e-5, f"step {step}: x differs by {diff:.3e}"
         assert torch.equal(a.hero_cache_view(0, B.VIEW_AGES), b.hero_cache_view(0, B.VIEW_AGES))
         for l in range(n_layers):
+            assert torch.equal(a.hero_cache_view(l, B.VIEW_S_CUR), b.hero_cache_view(l, B.VIEW_S_CUR)), (step, l)
+    a.close()
+    b.close()
+
+
+def test_the_42_layer_workload_step_matches_the_per_layer_calls():
+    """Config 4 as bench.py runs it (42 layers, 8 shallow, full step every 4th, 17 776 tokens):
+    six steps of hero_step against the per-layer entry points, each of which is checked against the
+    oracle at this shape above.  One set of weights serves every layer (the kernels and the schedule
+    do not care, and 42 sets would be 9.5 GB of host draws).  Selection against the oracle, caches
+    bit for bit, x up to the order of its fp32 additions (84 per row and step)."""
+    cfg = get_config("cvx5b_42l")
+    say("cvx5b_42l: hero_step vs per-layer calls over 6 steps (full at 0 and 4)")
+    w = make_layer_weights(cfg, 0, seed=0)
+    dev = {n: to_dev_bf16(w[n]) for n in w}
+    a, b = B.HeroCache(B.make_config(cfg)), B.HeroCache(B.make_config(cfg))
+    for l in range(cfg.n_layers):
+        a.hero_set_layer_weights(l, dev)
+        b.hero_set_layer_weights(l, dev)
+    n_sel = B.hero_num_selected(a.cfg)
+    idx = torch.empty(n_sel, dtype=torch.int32, device="cuda")
+    ages = np.zeros(cfg.n_video, np.int32)
+    x0 = make_tokens(cfg, seed=1)
+    last_full = 0
+    for step in range(6):
+        say(f"  step {step}")
+        xin = torch.from_numpy(x0 if step == 0 else perturb_tokens(x0, seed=20 + step, std=0.1)).cuda()
+        xa, xb = xin.clone(), xin.clone()
+        a.hero_step(xa, step)
+        if step % cfg.interval == 0:
+            last_full = step
+            for l in range(cfg.n_layers):
+                b.hero_full_layer(l, xb)
+            b.hero_reset_ages()
+            ages[:] = 0
+        else:
+            assert b.hero_select(step, idx) == n_sel
+            want_idx, ages = O.select(ages, cfg, step)
+            np.testing.assert_array_equal(idx.cpu().numpy(), want_idx)
+            np.testing.assert_array_equal(a.hero_cache_view(0, B.VIEW_IDX).cpu().numpy(), want_idx)
+            for l in range(cfg.n_shallow):
+                b.hero_refresh_layer(l, xb, idx, n_sel)
+            for l in range(cfg.n_shallow, cfg.n_layers):
+                b.hero_extrapolate_layer(l, xb, step - last_full)
+        torch.cuda.synchronize()
+        assert torch.isfinite(xa).all()
+        scale = float(xb.abs().max())
+        diff = float((xa - xb).abs().max())
+        assert diff <= 1e-5 * scale + 5e-5, f"step {step}: x differs by {diff:.3e} at |x| up to {scale:.1f}"
+        np.testing.assert_array_equal(a.hero_cache_view(0, B.VIEW_AGES).cpu().numpy(), ages)
+        assert torch.equal(a.hero_cache_view(0, B.VIEW_AGES), b.hero_cache_view(0, B.VIEW_AGES))
+        for l in range(cfg.n_layers):
             assert torch.equal(a.hero_cache_view(l, B.VIEW_S_CUR), b.hero_cache_view(l, B.VIEW_S_CUR)), (step, l)
     a.close()
     b.close()
