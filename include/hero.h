@@ -170,7 +170,10 @@ int hero_extrapolate_layer(hero_cache_t c, int32_t layer, void* dev_x, int32_t k
  * of x are read, so at large shapes hero_step updates those rows layer by layer
  * and adds the shallow layers' cached features to all other rows once, in the
  * same final pass; x equals the result of the per-layer calls up to fp32
- * summation order and the caches are identical. */
+ * summation order and the caches are identical.
+ * The call enqueues kernels only (no memsets, copies or synchronisation), so once every kernel has
+ * run eagerly it may be recorded under stream capture; the step number and k are launch scalars and
+ * the schedule state advances at record time, so a graph holds one position of the schedule. */
 int hero_step(hero_cache_t c, void* dev_x, int32_t step, void* stream);
 
 /* Read-only views into the handle, for tests and tools.  `what`:

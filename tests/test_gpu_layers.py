@@ -403,3 +403,47 @@ def test_full_layer_with_out_projection_and_ffn2_cut_along_k():
     assert_close(to_host_f64(xd) - x0.astype(np.float64), c.g_attn + c.g_ffn, "x increment", stored_parts=[c.g_attn])
     assert_close(to_host_f64(cache.hero_cache_view(0, B.VIEW_K)), c.k, "K")
     cache.close()
+
+
+def test_a_cached_step_can_be_captured_into_a_hip_graph_and_replayed():
+    """hero_step enqueues kernels only (no memsets, no copies, no synchronisation), so a caller may
+    capture it.  A captured cached step is replayed three times from the same device state, with
+    unrelated eager work and a synchronisation between the replays; every replay must reproduce the
+    eager step bit for bit, in x and in every byte of the cache (features, K/V, ages)."""
+    cfg = get_config("tiny", **MID)
+    say("cached step captured into a HIP graph, three replays against the eager step")
+    ws = [make_layer_weights(cfg, l, seed=0, std=0.04) for l in range(cfg.n_layers)]
+    x0 = torch.from_numpy(make_tokens(cfg, seed=1)).cuda()
+    x1 = torch.from_numpy(perturb_tokens(make_tokens(cfg, seed=1), seed=2, std=0.1)).cuda()
+
+    def after_full_step():
+        c = B.HeroCache(B.make_config(cfg))
+        upload_weights(c, cfg, ws)
+        x = x0.clone()
+        c.hero_step(x, 0)
+        torch.cuda.synchronize()
+        return c
+
+    eager = after_full_step()
+    xe = x1.clone()
+    eager.hero_step(xe, 1)
+    torch.cuda.synchronize()
+    assert eager.hero_cache_state() == (1, 0)
+
+    c = after_full_step()
+    before = c.cache_buf.clone()
+    xg = x1.clone()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        c.hero_step(xg, 1)                       # recorded, not run
+    for replay in range(3):
+        c.cache_buf.copy_(before)
+        xg.copy_(x1)
+        assert float((x0 * 2).sum()) == float((x0 * 2).sum())      # eager work and a synchronisation
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(xg, xe), f"replay {replay}: x"
+        assert torch.equal(c.cache_buf, eager.cache_buf), f"replay {replay}: cache"
+    del graph
+    eager.close()
+    c.close()
