@@ -137,7 +137,13 @@ hipError_t launch_select(const SelectGeom& g, int mode, uint32_t step_salt, int3
 }
 
 // ---------------------------------------------------------------------------------
-// gather + (optional add) + LayerNorm -> bf16 rows.  One wave per row.
+// gather + (optional add) + LayerNorm -> bf16 rows.
+// Rows of up to 1024 elements: one wave per row, four rows per workgroup (gather_ln_kernel).
+// Longer rows: one workgroup per row, each of its WPR waves holding 1024 elements or fewer (two
+// 8-element pieces per lane), the row statistics combined through LDS (gather_ln_split_kernel).
+// The kernel is bound by how the memory system takes its access stream, and many waves with
+// little state each are the better stream: at 3072 elements three waves per row move 5.7 TB/s
+// where one wave per row (48 elements per lane) moved 4.9.
 // ---------------------------------------------------------------------------------
 template <typename XT, int ITERS>
 __global__ __launch_bounds__(256) void gather_ln_kernel(
@@ -207,22 +213,113 @@ __global__ __launch_bounds__(256) void gather_ln_kernel(
   }
 }
 
+template <typename XT, int WPR>
+__global__ __launch_bounds__(64 * WPR) void gather_ln_split_kernel(
+    const XT* __restrict__ x, const bf16_t* __restrict__ add, const int32_t* __restrict__ rows,
+    int hidden, const bf16_t* __restrict__ gain, const bf16_t* __restrict__ bias,
+    float eps, bf16_t* __restrict__ out, LnMod mod) {
+  constexpr int ITERS = 2;
+  __shared__ float red[2][WPR];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = blockIdx.x;
+  const int64_t src = rows ? (int64_t)rows[r] : (int64_t)r;
+  // adaLN: the row's stream (text rows come first) picks the scale and shift vectors
+  const bf16_t* mscale = mod.scale_v ? (src < mod.n_text ? mod.scale_t : mod.scale_v) : nullptr;
+  const bf16_t* mshift = mod.scale_v ? (src < mod.n_text ? mod.shift_t : mod.shift_v) : nullptr;
+  const XT* xr = x + src * hidden;
+  const bf16_t* ar = add ? add + src * hidden : nullptr;
+  const int n_chunks = hidden >> 3;
+  const int c0 = wave * (ITERS * 64) + lane;      // this lane's pieces: c0 and c0 + 64
+  float v[ITERS][8];
+  float sum = 0.f;
+#pragma unroll
+  for (int it = 0; it < ITERS; ++it) {
+    const int c = c0 + it * 64;
+    if (c < n_chunks) {
+      ResidIO<XT>::load8(xr + c * 8, v[it]);
+      if (ar) {
+        float a8[8];
+        ResidIO<bf16_t>::load8(ar + c * 8, a8);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[it][j] += a8[j];
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) sum += v[it][j];
+    } else {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[it][j] = 0.f;
+    }
+  }
+  sum = wave_sum(sum);
+  if (lane == 0) red[0][wave] = sum;
+  __syncthreads();
+  float tot = 0.f;
+#pragma unroll
+  for (int i = 0; i < WPR; ++i) tot += red[0][i];
+  const float mean = tot / (float)hidden;
+  float sq = 0.f;
+#pragma unroll
+  for (int it = 0; it < ITERS; ++it) {
+    if (c0 + it * 64 < n_chunks) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) { float dlt = v[it][j] - mean; sq += dlt * dlt; }
+    }
+  }
+  sq = wave_sum(sq);
+  if (lane == 0) red[1][wave] = sq;
+  __syncthreads();
+  float tsq = 0.f;
+#pragma unroll
+  for (int i = 0; i < WPR; ++i) tsq += red[1][i];
+  const float rstd = rsqrtf(tsq / (float)hidden + eps);
+  bf16_t* orow = out + (int64_t)r * hidden;
+#pragma unroll
+  for (int it = 0; it < ITERS; ++it) {
+    const int c = c0 + it * 64;
+    if (c < n_chunks) {
+      float g8[8], b8[8], o8[8];
+      ResidIO<bf16_t>::load8(gain + c * 8, g8);
+      ResidIO<bf16_t>::load8(bias + c * 8, b8);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) o8[j] = (v[it][j] - mean) * rstd * g8[j] + b8[j];
+      if (mscale) {
+        float sc8[8], sh8[8];
+        ResidIO<bf16_t>::load8(mscale + c * 8, sc8);
+        ResidIO<bf16_t>::load8(mshift + c * 8, sh8);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) o8[j] = o8[j] * (1.0f + sc8[j]) + sh8[j];
+      }
+      ResidIO<bf16_t>::store8(orow + c * 8, o8);
+    }
+  }
+}
+
 template <typename XT>
 static hipError_t gather_ln_dispatch(const void* x, const bf16_t* add, const int32_t* rows, int n_rows,
                                      int hidden, const bf16_t* gain, const bf16_t* bias, float eps,
                                      bf16_t* out, const LnMod& mod, hipStream_t st) {
-  int iters = (hidden / 8 + 63) / 64;
-  dim3 grid((n_rows + 3) / 4), block(256);
+  const int iters = (hidden / 8 + 63) / 64;      // 8-element pieces per lane if one wave held the row
   const XT* xp = static_cast<const XT*>(x);
-#define LAUNCH(I)                                                                                   \
-  hipLaunchKernelGGL((gather_ln_kernel<XT, I>), grid, block, 0, st, xp, add, rows, n_rows, hidden, \
+  if (iters <= 2) {
+    dim3 grid((n_rows + 3) / 4), block(256);
+    if (iters <= 1)
+      hipLaunchKernelGGL((gather_ln_kernel<XT, 1>), grid, block, 0, st, xp, add, rows, n_rows, hidden, gain, bias, eps,
+                         out, mod);
+    else
+      hipLaunchKernelGGL((gather_ln_kernel<XT, 2>), grid, block, 0, st, xp, add, rows, n_rows, hidden, gain, bias, eps,
+                         out, mod);
+    return hipGetLastError();
+  }
+  const int wpr = (iters + 1) / 2;               // waves per row, two pieces per lane each (hidden <= 8192: <= 8)
+#define LAUNCH(W)                                                                                        \
+  hipLaunchKernelGGL((gather_ln_split_kernel<XT, W>), dim3(n_rows), dim3(64 * W), 0, st, xp, add, rows, hidden, \
                      gain, bias, eps, out, mod)
-  if (iters <= 1) LAUNCH(1);
-  else if (iters <= 2) LAUNCH(2);
-  else if (iters <= 4) LAUNCH(4);
-  else if (iters <= 6) LAUNCH(6);
-  else if (iters <= 8) LAUNCH(8);
-  else LAUNCH(16);
+  if (wpr <= 2) LAUNCH(2);
+  else if (wpr <= 3) LAUNCH(3);
+  else if (wpr <= 4) LAUNCH(4);
+  else if (wpr <= 6) LAUNCH(6);
+  else if (wpr <= 8) LAUNCH(8);
+  else return hipErrorInvalidValue;
 #undef LAUNCH
   return hipGetLastError();
 }
