@@ -220,7 +220,8 @@ int hero_gather_ln(const void* dev_x, int32_t x_dtype, const void* dev_add_bf16,
                    void* dev_out_bf16, void* stream);
 
 /* C[M,N] = act(A[M,K] W[N,K]^T + bias[N]) in bf16 with fp32 accumulation.
- * act: 0 none, 1 tanh-GELU.  K % 64 == 0, N % 64 == 0.  Operands are addressed with 32-bit byte
+ * act: 0 none, 1 tanh-GELU.  K % 64 == 0, N % 64 == 0.  All device pointers of the building blocks
+ * must be 16-byte aligned (index lists 4-byte), else HERO_ERR_INVALID_ARG.  Operands are addressed with 32-bit byte
  * offsets: (M + 512) * K * 2 and (N + 512) * K * 2 must stay below 2^32, else HERO_ERR_SHAPE. */
 int hero_linear(const void* dev_a, const void* dev_w, const void* dev_bias, void* dev_c,
                 int32_t m, int32_t n, int32_t k, int32_t act, void* stream);

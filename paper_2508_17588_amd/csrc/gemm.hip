@@ -26,6 +26,7 @@
 // accumulators hold the transposed block and V^T rows are written with row-contiguous
 // lanes.
 #include <algorithm>
+#include <atomic>
 #include <type_traits>
 
 #include "hero_device.h"
@@ -815,6 +816,48 @@ __device__ __forceinline__ void epilogue256(const GemmArgs& g, floatx16_t (&acc)
   }
 }
 
+// A kernel that uses more than 64 KB of dynamic LDS must be told so once on every device it runs
+// on.  `done` holds one bit per device ordinal (devices past 63 are told on every launch); the
+// runtime call is idempotent, so two host threads that meet here at most repeat it.
+hipError_t allow_dynamic_lds(const void* kern, int bytes, std::atomic<uint64_t>& done) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const uint64_t bit = dev < 64 ? 1ull << dev : 0;
+  if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
+  e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess) done.fetch_or(bit, std::memory_order_release);
+  return e;
+}
+
+// The chip runs 256 workgroups at a time, so the last round of tiles may leave most of it
+// idle.  Cutting those n_rem tiles into s k-chunks makes the round take ceil(n_rem*s/256)/s of
+// a tile's time, and costs a fix-up pass that moves n_rem*s blocks of 256 KB twice (about
+// 0.1*n_rem/stages of a tile's time per chunk, measured).  Take the s that minimises the sum,
+// with chunks of at least 16 stages, among those whose partial sums fit ws_bytes.  At the
+// 17776-token shapes this cuts FFN2 (k = 12288; 3 rounds + 72 tiles) in 3 and makes it 9 %
+// faster; the out-projection (k = 3072, the same tiles) is cut in 2 for 3 %, FFN1 (13 rounds +
+// 32 tiles) in 3 for 0.4 %.  Returns the number of k-chunks (1: no cut); *n_rem_out: the tile
+// slots of the last round.
+int choose_k_split(const GemmArgs& g, size_t ws_bytes, int* n_rem_out) {
+  const int tiles_m = (g.m + 255) / 256, tiles_n = (g.n + 255) / 256;
+  const int slots = (tiles_m * tiles_n + 7) / 8 * 8;
+  const int n_rem = slots - slots / 256 * 256;
+  *n_rem_out = n_rem;
+  // (the QKV projection is never cut: its k is the hidden size, too short to pay at the supported sizes)
+  if (g.epilogue == EPI_QKV || n_rem == 0) return 1;
+  const int stages = g.k / SBK;
+  const int s_max = (int)std::min<size_t>((size_t)std::min(stages / 16, 8), ws_bytes / ((size_t)n_rem * 262144));
+  const double per_chunk = 0.1 * n_rem / stages;
+  double best = 1.0;
+  int split = 1;
+  for (int sp = 2; sp <= s_max; ++sp) {
+    const double t = (double)((n_rem * sp + 255) / 256) / sp + per_chunk * sp;
+    if (t < best - 0.02) { best = t; split = sp; }
+  }
+  return split;
+}
+
 hipError_t launch_gemm256(const GemmArgs& g, hipStream_t st) {
   int tiles_m = (g.m + 255) / 256, tiles_n = (g.n + 255) / 256;
   int n_tiles = tiles_m * tiles_n;
@@ -825,30 +868,11 @@ hipError_t launch_gemm256(const GemmArgs& g, hipStream_t st) {
   // groups (in-session A/B at the 5B shapes: QKV of 4485 rows 4 % faster with 4, the 17776-row
   // problems with k = 3072 0.5 % faster with 8, 16 is 1-7 % slower everywhere).
   const int group_m = (g.k >= 8192 || tiles_m <= 24) ? 4 : 8;
-  // The chip runs 256 workgroups at a time, so the last round of tiles may leave most of it
-  // idle.  Cutting those n_rem tiles into s k-chunks makes the round take ceil(n_rem*s/256)/s of
-  // a tile's time, and costs a fix-up pass that moves n_rem*s blocks of 256 KB twice (about
-  // 0.1*n_rem/stages of a tile's time per chunk, measured).  Take the s that minimises the sum,
-  // with chunks of at least 16 stages.  At the 17776-token shapes this cuts FFN2 (k = 12288;
-  // 3 rounds + 72 tiles) in 3 and makes it 9 % faster; the out-projection (k = 3072, the same
-  // tiles) is cut in 2 for 3 %, FFN1 (13 rounds + 32 tiles) in 3 for 0.4 %.
   SplitK sk;
   sk.full_items = slots / 256 * 256;
-  sk.split = 1;
   sk.ws = g.splitk_ws;
-  const int n_rem = slots - sk.full_items;
-  // (the QKV projection is never cut: its k is the hidden size, too short to pay at the supported sizes)
-  if (g.splitk_ws != nullptr && g.epilogue != EPI_QKV && n_rem > 0) {
-    const int stages = g.k / SBK;
-    const int s_max = (int)std::min<size_t>((size_t)std::min(stages / 16, 8),
-                                            g.splitk_ws_bytes / ((size_t)n_rem * 262144));
-    const double per_chunk = 0.1 * n_rem / stages;
-    double best = 1.0;
-    for (int sp = 2; sp <= s_max; ++sp) {
-      const double t = (double)((n_rem * sp + 255) / 256) / sp + per_chunk * sp;
-      if (t < best - 0.02) { best = t; sk.split = sp; }
-    }
-  }
+  int n_rem = 0;
+  sk.split = choose_k_split(g, g.splitk_ws != nullptr ? g.splitk_ws_bytes : 0, &n_rem);
   if (sk.split == 1) sk.full_items = slots;
   const int n_split_tiles = slots - sk.full_items;
   dim3 grid(sk.full_items + n_split_tiles * sk.split), block(512);
@@ -856,13 +880,9 @@ hipError_t launch_gemm256(const GemmArgs& g, hipStream_t st) {
   do {                                                                                                   \
     auto kern = gemm256_kernel<E>;                                                                       \
     auto fix = gemm256_fixup_kernel<E>;                                                                  \
-    static bool attr_set = false;                                                                        \
-    if (!attr_set) {                                                                                     \
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                            \
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, GEMM256_LDS);       \
-      if (e != hipSuccess) return e;                                                                     \
-      attr_set = true;                                                                                   \
-    }                                                                                                    \
+    static std::atomic<uint64_t> lds_allowed{0};                                                         \
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(kern), GEMM256_LDS, lds_allowed);     \
+    if (e != hipSuccess) return e;                                                                       \
     hipLaunchKernelGGL(kern, grid, block, GEMM256_LDS, st, g, tiles_m, tiles_n, per_xcd, group_m, sk);   \
     if (n_split_tiles > 0)                                                                               \
       hipLaunchKernelGGL(fix, dim3(n_split_tiles * 8), dim3(64), STAGE_REGION, st, g, tiles_m, tiles_n,  \
@@ -891,13 +911,9 @@ hipError_t launch_cfg(const GemmArgs& g, hipStream_t st) {
 #define HERO_GEMM_LAUNCH(E)                                                                              \
   do {                                                                                                   \
     auto kern = gemm_kernel<BM, BN, WM, WN, E>;                                                          \
-    static bool attr_set = false;                                                                        \
-    if (!attr_set) {                                                                                     \
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                            \
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);         \
-      if (e != hipSuccess) return e;                                                                     \
-      attr_set = true;                                                                                   \
-    }                                                                                                    \
+    static std::atomic<uint64_t> lds_allowed{0};                                                         \
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(kern), (int)smem, lds_allowed);       \
+    if (e != hipSuccess) return e;                                                                       \
     hipLaunchKernelGGL(kern, grid, block, smem, st, g, tiles_m, tiles_n, per_xcd);                       \
   } while (0)
   switch (g.epilogue) {
@@ -923,6 +939,13 @@ bool uses_large_tiles(const GemmArgs& g) {
   return big_tiles >= 128 && qkv_split_ok;
 }
 }  // namespace
+
+size_t gemm_wanted_scratch_bytes(const GemmArgs& g) {
+  if (g.m <= 0 || g.n <= 0 || g.k <= 0 || !uses_large_tiles(g)) return 0;
+  int n_rem = 0;
+  const int split = choose_k_split(g, (size_t)-1, &n_rem);
+  return split > 1 ? (size_t)n_rem * split * 262144 : 0;
+}
 
 bool gemm_can_update_x(const GemmArgs& g) { return g.epilogue == EPI_SCATTER_ADD && uses_large_tiles(g); }
 

@@ -5,6 +5,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <initializer_list>
 #include <cstring>
 #include <new>
 #include <algorithm>
@@ -33,6 +34,13 @@ int fail(int code, const char* fmt, ...) {
   } while (0)
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// true when every pointer is null or 16-byte aligned (the kernels use 8- and 16-byte vector accesses)
+bool aligned16(std::initializer_list<const void*> ptrs) {
+  for (const void* p : ptrs)
+    if ((uintptr_t)p & 15) return false;
+  return true;
+}
 
 uint32_t fmix32_host(uint32_t h) {
   h ^= h >> 16; h *= 0x85EBCA6Bu;
@@ -788,20 +796,30 @@ int hero_gather_ln(const void* dev_x, int32_t x_dtype, const void* dev_add_bf16,
   if (x_dtype != HERO_DTYPE_FP32 && x_dtype != HERO_DTYPE_BF16) return fail(HERO_ERR_INVALID_ARG, "bad x_dtype");
   if (n_rows < 0) return fail(HERO_ERR_INVALID_ARG, "n_rows < 0");
   if (hidden < 8 || hidden % 8 != 0 || hidden > 8192) return fail(HERO_ERR_SHAPE, "hidden must be a multiple of 8, <= 8192");
+  if (!aligned16({dev_x, dev_add_bf16, gain, bias, dev_out_bf16}) || ((uintptr_t)dev_rows & 3))
+    return fail(HERO_ERR_INVALID_ARG, "x, add, gain, bias and out must be 16-byte aligned, rows 4-byte aligned");
   HIP_TRY(launch_gather_ln(dev_x, x_dtype == HERO_DTYPE_FP32, (const bf16_t*)dev_add_bf16, dev_rows, n_rows, hidden,
                            (const bf16_t*)gain, (const bf16_t*)bias, eps, (bf16_t*)dev_out_bf16, (hipStream_t)stream));
   return HERO_OK;
 }
 
-int hero_linear_scratch(const void* dev_a, const void* dev_w, const void* dev_bias, void* dev_c, int32_t m,
-                        int32_t n, int32_t k, int32_t act, void* dev_scratch, size_t scratch_bytes, void* stream) {
+static int check_linear_args(const void* dev_a, const void* dev_w, const void* dev_bias, void* dev_c, int32_t m,
+                             int32_t n, int32_t k, int32_t act) {
   if (!dev_w || !dev_bias || (m > 0 && (!dev_a || !dev_c))) return fail(HERO_ERR_INVALID_ARG, "null pointer");
   if (m < 0 || n <= 0 || k <= 0) return fail(HERO_ERR_INVALID_ARG, "bad sizes");
   if (k % 64 != 0 || n % 64 != 0) return fail(HERO_ERR_SHAPE, "k and n must be multiples of 64");
   if (act != 0 && act != 1) return fail(HERO_ERR_INVALID_ARG, "act must be 0 or 1");
   if (!gemm_offsets_fit(m, n, k))
     return fail(HERO_ERR_SHAPE, "(m + 512) * k * 2 and (n + 512) * k * 2 must stay below 2^32 (32-bit operand offsets)");
-  if (dev_scratch != nullptr && (uintptr_t)dev_scratch % 16 != 0) return fail(HERO_ERR_INVALID_ARG, "scratch must be 16-byte aligned");
+  if (!aligned16({dev_a, dev_w, dev_bias, dev_c})) return fail(HERO_ERR_INVALID_ARG, "a, w, bias and c must be 16-byte aligned");
+  return HERO_OK;
+}
+
+int hero_linear_scratch(const void* dev_a, const void* dev_w, const void* dev_bias, void* dev_c, int32_t m,
+                        int32_t n, int32_t k, int32_t act, void* dev_scratch, size_t scratch_bytes, void* stream) {
+  int rc = check_linear_args(dev_a, dev_w, dev_bias, dev_c, m, n, k, act);
+  if (rc) return rc;
+  if (!aligned16({dev_scratch})) return fail(HERO_ERR_INVALID_ARG, "scratch must be 16-byte aligned");
   GemmArgs g;
   memset(&g, 0, sizeof(g));
   g.a = (const bf16_t*)dev_a; g.w = (const bf16_t*)dev_w; g.bias = (const bf16_t*)dev_bias;
@@ -829,7 +847,8 @@ int hero_attention_scratch(const void* dev_q, const void* dev_k, const void* dev
   a.q = (const bf16_t*)dev_q; a.k = (const bf16_t*)dev_k; a.vt = (const bf16_t*)dev_vt; a.ld_vt = ld_vt;
   a.o = (bf16_t*)dev_o; a.r = r; a.n_keys = n_keys; a.n_heads = n_heads; a.head_dim = head_dim;
   a.q_scale = 1.4426950408889634f / sqrtf((float)head_dim);
-  if (dev_scratch != nullptr && (uintptr_t)dev_scratch % 16 != 0) return fail(HERO_ERR_INVALID_ARG, "scratch must be 16-byte aligned");
+  if (!aligned16({dev_q, dev_k, dev_vt, dev_o, dev_scratch}))
+    return fail(HERO_ERR_INVALID_ARG, "q, k, vt, o and scratch must be 16-byte aligned");
   a.split_ws = (float*)dev_scratch; a.split_ws_bytes = dev_scratch ? scratch_bytes : 0;
   HIP_TRY(launch_attention(a, (hipStream_t)stream));
   return HERO_OK;
@@ -845,6 +864,7 @@ int hero_axpy_features(void* dev_x, int32_t x_dtype, const void* s_cur, const vo
   if (n_elems > 0 && (!dev_x || !s_cur)) return fail(HERO_ERR_INVALID_ARG, "null pointer");
   if (x_dtype != HERO_DTYPE_FP32 && x_dtype != HERO_DTYPE_BF16) return fail(HERO_ERR_INVALID_ARG, "bad x_dtype");
   if (n_elems < 0 || n_elems % 8 != 0) return fail(HERO_ERR_SHAPE, "n_elems must be a non-negative multiple of 8");
+  if (!aligned16({dev_x, s_cur, s_prev})) return fail(HERO_ERR_INVALID_ARG, "x, s_cur and s_prev must be 16-byte aligned");
   HIP_TRY(launch_axpy_features(dev_x, x_dtype == HERO_DTYPE_FP32, (const bf16_t*)s_cur, (const bf16_t*)s_prev, alpha,
                                n_elems, (hipStream_t)stream));
   return HERO_OK;
@@ -859,6 +879,7 @@ int hero_second_diff_stats(const void* f_prev, const void* f_cur, const void* f_
     return fail(HERO_ERR_BUFFER_TOO_SMALL, "scratch has %zu bytes, %zu needed", scratch_bytes, second_diff_scratch_bytes());
   if ((uintptr_t)dev_scratch % 8 != 0 || (uintptr_t)dev_stats % 8 != 0)
     return fail(HERO_ERR_INVALID_ARG, "scratch and stats must be 8-byte aligned");
+  if (!aligned16({f_prev, f_cur, f_next})) return fail(HERO_ERR_INVALID_ARG, "the feature arrays must be 16-byte aligned");
   HIP_TRY(launch_second_diff_stats((const bf16_t*)f_prev, (const bf16_t*)f_cur, (const bf16_t*)f_next, n_elems,
                                    (double*)dev_scratch, dev_stats, accumulate != 0, (hipStream_t)stream));
   return HERO_OK;

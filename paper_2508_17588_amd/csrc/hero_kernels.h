@@ -99,6 +99,8 @@ struct GemmArgs {
 };
 
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t st);
+// bytes of scratch launch_gemm would use for this problem if it had all it wanted (0: the problem is not cut along k)
+size_t gemm_wanted_scratch_bytes(const GemmArgs& g);
 // whether launch_gemm would honour g.x for this problem (only the large-tile kernel does)
 bool gemm_can_update_x(const GemmArgs& g);
 

@@ -133,6 +133,12 @@ def test_null_and_small_buffers_are_rejected_before_any_gpu_work(lib):
     p = ctypes.c_void_p(256)
     assert lib.hero_linear(p, p, p, p, 1, 60, 64, 0, None) == B.HERO_ERR_SHAPE
     assert lib.hero_linear_scratch(p, p, p, p, 1, 64, 64, 0, ctypes.c_void_p(260), 1 << 20, None) == B.HERO_ERR_INVALID_ARG
+    # misaligned operands
+    q = ctypes.c_void_p(264)
+    assert lib.hero_linear(q, p, p, p, 1, 64, 64, 0, None) == B.HERO_ERR_INVALID_ARG
+    assert lib.hero_attention(p, q, p, 128, p, 1, 100, 1, 64, None) == B.HERO_ERR_INVALID_ARG
+    assert lib.hero_axpy_features(p, 1, q, None, 0.0, 16, None) == B.HERO_ERR_INVALID_ARG
+    assert lib.hero_gather_ln(p, 1, None, None, 1, 64, p, q, 1e-5, p, None) == B.HERO_ERR_INVALID_ARG
     assert lib.hero_attention(p, p, p, 100, p, 1, 100, 1, 64, None) == B.HERO_ERR_SHAPE
     assert lib.hero_attention(p, p, p, 128, p, 1, 100, 1, 48, None) == B.HERO_ERR_SHAPE
     # operand sizes beyond the kernels' 32-bit offsets
