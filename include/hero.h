@@ -236,6 +236,19 @@ int hero_linear_scratch(const void* dev_a, const void* dev_w, const void* dev_bi
                         int32_t m, int32_t n, int32_t k, int32_t act, void* dev_scratch,
                         size_t scratch_bytes, void* stream);
 
+/* For callers that cannot allocate device memory or pass a workspace (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): hero_linear_scratch with the partial sums
+ * kept in a 32 MiB array that lives inside the library's code object, one copy per device, held
+ * until the process ends.  The call allocates and frees nothing (the first call on a device looks
+ * the array's device address up once).  Same product, same cut and therefore bit-identical results
+ * to hero_linear_scratch with a 32 MiB scratch.  A problem whose k-split wants more than the array
+ * holds (tile slots of the last round x k-chunks x 256 KiB > 32 MiB) is refused with
+ * HERO_ERR_BUFFER_TOO_SMALL and launches nothing.  Nothing in the array has to start at zero (every
+ * block is written before it is read), but all calls on one device share it: calls that overlap in
+ * time on one device (two streams, two host threads) race and must be ordered by the caller. */
+int hero_linear_static(const void* dev_a, const void* dev_w, const void* dev_bias, void* dev_c,
+                       int32_t m, int32_t n, int32_t k, int32_t act, void* stream);
+
 /* O[r,hidden] = softmax(Q K^T / sqrt(head_dim)) V per head; Q [r,hidden], K [n_keys,hidden],
  * V given transposed as vt [hidden, ld_vt] with ld_vt >= n_keys, ld_vt % 64 == 0 and
  * columns n_keys..ld_vt-1 finite (zero).  (FullAttn of Eq. 2 for refreshed queries, Eq. 3.)

@@ -38,7 +38,7 @@ EXPORTS = (
     "hero_last_error", "hero_num_selected", "hero_cache_bytes", "hero_cache_create",
     "hero_cache_destroy", "hero_cache_reset", "hero_set_layer_weights", "hero_full_layer",
     "hero_select", "hero_reset_ages", "hero_refresh_layer", "hero_extrapolate_layer", "hero_step",
-    "hero_cache_view", "hero_cache_state", "hero_profile_begin", "hero_profile_begin_kinds", "hero_profile_end", "hero_gather_ln", "hero_linear", "hero_linear_scratch",
+    "hero_cache_view", "hero_cache_state", "hero_profile_begin", "hero_profile_begin_kinds", "hero_profile_end", "hero_gather_ln", "hero_linear", "hero_linear_scratch", "hero_linear_static",
     "hero_attention", "hero_attention_scratch",
     "hero_axpy_features", "hero_second_diff_stats", "hero_stability_scores",
 )
@@ -99,6 +99,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
         "hero_gather_ln": [P, I, P, P, I, I, P, P, c_float, P, P],
         "hero_linear": [P, P, P, P, I, I, I, I, P],
         "hero_linear_scratch": [P, P, P, P, I, I, I, I, P, ctypes.c_size_t, P],
+        "hero_linear_static": [P, P, P, P, I, I, I, I, P],
         "hero_attention": [P, P, P, c_int64, P, I, I, I, I, P],
         "hero_attention_scratch": [P, P, P, c_int64, P, I, I, I, I, P, ctypes.c_size_t, P],
         "hero_axpy_features": [P, I, P, P, c_float, c_int64, P],
@@ -327,6 +328,18 @@ def hero_linear_scratch(a, w, bias, c, scratch, act: int = 0):
         raise ValueError("scratch must be a contiguous device tensor")
     _check(load_library().hero_linear_scratch(_ptr(a), _ptr(w), _ptr(bias), _ptr(c), m, n, k, act, _ptr(scratch),
                                               scratch.numel() * scratch.element_size(), _stream()))
+
+
+def hero_linear_static(a, w, bias, c, act: int = 0):
+    """hero_linear_scratch with the library's own 32 MiB scratch: the call allocates nothing."""
+    import torch
+    for t, n in ((a, "a"), (w, "w"), (bias, "bias"), (c, "c")):
+        _need(t, torch.bfloat16, n)
+    m, k = a.shape
+    n = w.shape[0]
+    if w.shape[1] != k or bias.numel() != n or c.numel() < m * n:
+        raise ValueError("shape mismatch")
+    _check(load_library().hero_linear_static(_ptr(a), _ptr(w), _ptr(bias), _ptr(c), m, n, k, act, _stream()))
 
 
 def hero_attention(q, k, vt, o, n_keys: int, n_heads: int, head_dim: int, scratch=None):

@@ -7,6 +7,7 @@
 #include <cstdio>
 #include <initializer_list>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <algorithm>
 #include <utility>
@@ -40,6 +41,32 @@ bool aligned16(std::initializer_list<const void*> ptrs) {
   for (const void* p : ptrs)
     if ((uintptr_t)p & 15) return false;
   return true;
+}
+
+// ---- scratch owned by the library, for the entry point that must not allocate -----------------
+// Every device the library runs on holds its own copy of this array, at its own address, until
+// the process ends.  In host code the array's name is only a handle for hipGetSymbolAddress: the
+// device address is looked up once per device and that pointer is what kernels are given.
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)32 << 20;
+constexpr int STATIC_SCRATCH_MAX_DEVICES = 64;
+static __device__ __attribute__((used)) __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+int static_scratch(void** out) {
+  static std::mutex mu;
+  static void* ptrs[STATIC_SCRATCH_MAX_DEVICES] = {};
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= STATIC_SCRATCH_MAX_DEVICES)
+    return fail(HERO_ERR_INVALID_ARG, "device ordinal %d outside [0, %d)", dev, STATIC_SCRATCH_MAX_DEVICES);
+  std::lock_guard<std::mutex> lock(mu);
+  if (ptrs[dev] == nullptr) {
+    void* p = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));      // the current device's copy
+    if (p == nullptr) return fail(HERO_ERR_HIP, "hipGetSymbolAddress returned a null address");
+    ptrs[dev] = p;
+  }
+  *out = ptrs[dev];
+  return HERO_OK;
 }
 
 uint32_t fmix32_host(uint32_t h) {
@@ -832,6 +859,26 @@ int hero_linear_scratch(const void* dev_a, const void* dev_w, const void* dev_bi
 int hero_linear(const void* dev_a, const void* dev_w, const void* dev_bias, void* dev_c, int32_t m, int32_t n,
                 int32_t k, int32_t act, void* stream) {
   return hero_linear_scratch(dev_a, dev_w, dev_bias, dev_c, m, n, k, act, nullptr, 0, stream);
+}
+
+int hero_linear_static(const void* dev_a, const void* dev_w, const void* dev_bias, void* dev_c, int32_t m, int32_t n,
+                       int32_t k, int32_t act, void* stream) {
+  int rc = check_linear_args(dev_a, dev_w, dev_bias, dev_c, m, n, k, act);
+  if (rc) return rc;
+  if (m == 0) return HERO_OK;
+  // what hero_linear_scratch would want for this problem; anything beyond the library's array is refused
+  GemmArgs g;
+  memset(&g, 0, sizeof(g));
+  g.m = m; g.n = n; g.k = k; g.epilogue = act ? EPI_GELU : EPI_PLAIN;
+  const size_t want = gemm_wanted_scratch_bytes(g);
+  if (want > STATIC_SCRATCH_BYTES)
+    return fail(HERO_ERR_BUFFER_TOO_SMALL,
+                "hero_linear_static: the k-split of this %d x %d x %d problem needs %zu bytes of partial sums, the "
+                "library's own scratch holds %zu; use hero_linear_scratch with a buffer of yours",
+                m, n, k, want, STATIC_SCRATCH_BYTES);
+  void* ws = nullptr;
+  if ((rc = static_scratch(&ws)) != HERO_OK) return rc;
+  return hero_linear_scratch(dev_a, dev_w, dev_bias, dev_c, m, n, k, act, ws, STATIC_SCRATCH_BYTES, stream);
 }
 
 int hero_attention_scratch(const void* dev_q, const void* dev_k, const void* dev_vt, int64_t ld_vt, void* dev_o,

@@ -133,6 +133,10 @@ def test_null_and_small_buffers_are_rejected_before_any_gpu_work(lib):
     p = ctypes.c_void_p(256)
     assert lib.hero_linear(p, p, p, p, 1, 60, 64, 0, None) == B.HERO_ERR_SHAPE
     assert lib.hero_linear_scratch(p, p, p, p, 1, 64, 64, 0, ctypes.c_void_p(260), 1 << 20, None) == B.HERO_ERR_INVALID_ARG
+    # the no-allocation GEMM refuses a k-split that its own 32 MiB array cannot hold, before any launch
+    assert lib.hero_linear_static(p, p, p, p, 17776, 3072, 12288, 0, None) == B.HERO_ERR_BUFFER_TOO_SMALL
+    assert b"hero_linear_scratch" in lib.hero_last_error()
+    assert lib.hero_linear_static(p, p, p, p, 1, 60, 64, 0, None) == B.HERO_ERR_SHAPE
     # misaligned operands
     q = ctypes.c_void_p(264)
     assert lib.hero_linear(q, p, p, p, 1, 64, 64, 0, None) == B.HERO_ERR_INVALID_ARG
