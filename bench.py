@@ -25,7 +25,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 def parse():
     p = argparse.ArgumentParser()
     p.add_argument("--gpus", type=int, default=1)
-    p.add_argument("--steps", type=int, default=50)
+    p.add_argument("--steps", type=int, default=None, help="denoising steps to time (default: the workload's schedule length)")
     p.add_argument("--warmup", type=int, default=2)
     p.add_argument("--workload", default="cvx5b_42l")
     p.add_argument("--block-flags", type=int, default=0,
@@ -35,7 +35,11 @@ def parse():
     p.add_argument("--ratio", choices=("10", "25", "50"), default=None,
                    help="refresh ratio in percent, with the patch shape of the one-block ratio sweep")
     p.add_argument("--no-cpu-baseline", action="store_true")
-    p.add_argument("--cpu-sample-rows", type=int, default=4485)
+    p.add_argument("--cpu-sample-rows", type=int, default=4096,
+                   help="rows of the CPU oracle's samples: half of them per row-sampled piece")
+    p.add_argument("--score-scale", action="store_true",
+                   help="after the timed region, run refreshed-query attention at growing score magnitudes and "
+                        "report time and fallback counts (the price of the running-maximum path)")
     return p.parse_args()
 
 
@@ -67,38 +71,132 @@ def device_weights(cfg, torch, gen):
 
 
 def cpu_baseline(cfg, w0, x0_host, n_rows, n_steps):
-    """Times the CPU oracle (as it stands) on a bounded sample: one refresh-layer call on
-    the first n_rows selected rows of one layer at the real shape, against a synthetic
-    filled cache; scales to ms per denoising step by the FLOPs ratio."""
+    """The CPU oracle as it stands, timed on a bounded sample of the workload and scaled by call
+    counts (labelled "extrapolated"): the three layer operations of Alg. 1 at the real shape,
+      full layer      -- LayerNorm + K/V projection of all N rows (this also fills the sample's
+                         cache with real values), the Q projection and attention of 4 of the heads
+                         over all rows, and out-projection + LN2 + FFN on n_rows/2 rows;
+      refresh layer   -- oracle.refresh_layer on n_rows/2 of the selected rows against that cache;
+      extrapolation   -- oracle.extrapolate_layer on two full [N, hidden] generations.
+    Each piece is scaled to the whole operation (by heads or by rows: the oracle's cost is linear in
+    both) and multiplied by how often the schedule calls it."""
     import numpy as np
     from threadpoolctl import threadpool_info
     from oracle import hero_oracle as O
 
-    rng = np.random.default_rng(7)
-    n, d = cfg.n_tokens, cfg.hidden
+    n, d, hd = cfg.n_tokens, cfg.hidden, cfg.head_dim
     w64 = {k: v.astype(np.float64) for k, v in w0.items()}
+    x = x0_host.astype(np.float64)
+    n_part = max(64, n_rows // 2)
+    heads_s = min(4, cfg.n_heads)
+    t = {}
+    t0 = time.perf_counter()
+    u = O.layer_norm(x, w64["ln1_g"], w64["ln1_b"], cfg.ln_eps)
+    kv = O.linear(u, w64["w_qkv"][d:], w64["b_qkv"][d:])
+    t["ln1 + K/V projection, all rows"] = time.perf_counter() - t0
     cache = O.LayerCache()
-    cache.k = rng.standard_normal((n, d))
-    cache.v = rng.standard_normal((n, d))
+    cache.k, cache.v = np.ascontiguousarray(kv[:, :d]), np.ascontiguousarray(kv[:, d:])
+    t0 = time.perf_counter()
+    cs = heads_s * hd
+    q_s = O.linear(u, w64["w_qkv"][:cs], w64["b_qkv"][:cs])
+    o_s = O.attention(q_s, cache.k[:, :cs], cache.v[:, :cs], heads_s)
+    t_heads = time.perf_counter() - t0
+    t[f"Q projection + attention, {heads_s} of {cfg.n_heads} heads, all rows"] = t_heads
+    rows = np.arange(0, n, max(1, n // n_part))[:n_part]
+    o_rows = np.tile(o_s[rows], (1, cfg.n_heads // heads_s))
+    t0 = time.perf_counter()
+    g_attn = O.linear(o_rows, w64["w_o"], w64["b_o"])
+    g_ffn = O.ffn(O.layer_norm(x[rows] + g_attn, w64["ln2_g"], w64["ln2_b"], cfg.ln_eps), w64)
+    t_rest = time.perf_counter() - t0
+    t[f"out-projection + LN2 + FFN, {len(rows)} rows"] = t_rest
+    full_layer_s = t["ln1 + K/V projection, all rows"] + t_heads * cfg.n_heads / heads_s + t_rest * n / len(rows)
+
+    rng = np.random.default_rng(7)
     cache.g_attn = rng.standard_normal((n, d)) * 0.1
     cache.g_ffn = rng.standard_normal((n, d)) * 0.1
     idx, _ = O.select(np.zeros(cfg.n_video, np.int32), cfg, 1)
-    idx = idx[:n_rows]
-    x = x0_host.astype(np.float64)
+    n_sel = len(idx)
+    sub = idx[:n_part]
     t0 = time.perf_counter()
-    O.refresh_layer(x, w64, cache, idx, cfg.n_heads, cfg.ln_eps)
-    dt = time.perf_counter() - t0
-    sample_flops = O.layer_flops(len(idx), n, d, cfg.ffn_dim)
-    step_flops = O.schedule_flops(cfg, n_steps) / n_steps
+    O.refresh_layer(x, w64, cache, sub, cfg.n_heads, cfg.ln_eps)
+    t_ref = time.perf_counter() - t0
+    t[f"refresh_layer, {len(sub)} of {n_sel} selected rows"] = t_ref
+    refresh_layer_s = t_ref * n_sel / max(1, len(sub))
+
+    cache.g_attn_prev, cache.g_ffn_prev = cache.g_ffn, cache.g_attn      # a second generation of the same size
+    t0 = time.perf_counter()
+    O.extrapolate_layer(x, cache, 1, cfg.interval)
+    extrap_layer_s = time.perf_counter() - t0
+    t["extrapolate_layer, all rows"] = extrap_layer_s
+
+    n_full = sum(1 for s_ in range(n_steps) if s_ % cfg.interval == 0)
+    n_cached = n_steps - n_full
+    total = (n_full * cfg.n_layers * full_layer_s +
+             n_cached * (cfg.n_shallow * refresh_layer_s + (cfg.n_layers - cfg.n_shallow) * extrap_layer_s))
     cores = max([i.get("num_threads", 1) for i in threadpool_info() if i.get("user_api") == "blas"] or [1])
     return {
-        "value": dt * 1e3 * step_flops / sample_flops, "unit": "ms per denoising step (extrapolated by FLOPs)",
+        "value": total * 1e3 / n_steps, "unit": "ms per denoising step (extrapolated from per-layer oracle times x call counts)",
         "cores": cores, "kind": "oracle",
-        "sample": f"oracle refresh_layer (float64 numpy) on {len(idx)} of the selected rows of one "
-                  f"{cfg.hidden}-wide layer against all {n} cached keys: {dt:.2f} s for "
-                  f"{sample_flops / 1e12:.3f} TFLOP; one mean step of the schedule is {step_flops / 1e12:.1f} TFLOP",
-        "sample_seconds": dt,
+        "sample": "float64 numpy oracle at the workload's shape; " + "; ".join(f"{k}: {v:.2f} s" for k, v in t.items()) +
+                  f"; scaled: full layer {full_layer_s:.1f} s, refresh layer {refresh_layer_s:.1f} s, extrapolated layer "
+                  f"{extrap_layer_s:.2f} s; schedule of {n_steps} steps = {n_full} full x {cfg.n_layers} layers + {n_cached} cached x "
+                  f"({cfg.n_shallow} refreshed + {cfg.n_layers - cfg.n_shallow} extrapolated layers)",
+        "sample_seconds": sum(t.values()),
+        "per_layer_seconds": {"full": full_layer_s, "refresh": refresh_layer_s, "extrapolate": extrap_layer_s},
     }
+
+
+def kernel_sources_sha():
+    """Hash of the kernel sources, to tell whether a stored counter profile is of this build."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2508_17588_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".hip", ".h")):
+            h.update(name.encode())
+            h.update(open(os.path.join(csrc, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
+# what BASELINE.json's north_star asks of each kind of kernel, as a fraction of the chip's peak
+TARGETS = {"gemm_qkv/cached": 0.50, "gemm_o/cached": 0.50, "gemm_ff1/cached": 0.50, "gemm_ff2/cached": 0.50,
+           "attention/cached": 0.50, "ln/cached": 0.70, "extrap/cached": 0.70, "extrap_layer/standalone": 0.70}
+
+
+def attention_fallback_legs(cfg, torch, B):
+    """Refreshed-query attention at the workload's shape with q.k scores of growing magnitude: the
+    head_dim-64 kernel evaluates softmax without a running maximum and recomputes a workgroup
+    (256 queries of one head) with the running-maximum form when a row sum leaves [2^-80, 2^80].
+    sigma is the standard deviation of a score in log2 units (1.44 for unit-variance q and k)."""
+    d, n = cfg.hidden, cfg.n_tokens
+    r = B.hero_num_selected(B.make_config(cfg)) or n
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(5)
+    k = torch.randn(n, d, generator=gen, device="cuda").to(torch.bfloat16)
+    ld = (n + 63) // 64 * 64
+    vt = torch.zeros(d, ld, device="cuda", dtype=torch.bfloat16)
+    vt[:, :n] = torch.randn(d, n, generator=gen, device="cuda").to(torch.bfloat16)
+    q0 = torch.randn(r, d, generator=gen, device="cuda")
+    o = torch.empty(r, d, device="cuda", dtype=torch.bfloat16)
+    scratch = torch.empty(128 << 18, device="cuda", dtype=torch.float32)
+    count = torch.zeros(1, dtype=torch.int32, device="cuda")
+    n_wg = (r + 255) // 256 * cfg.n_heads
+    legs = []
+    for sigma in (1.44, 8.0, 12.0, 16.0, 32.0):
+        q = (q0 * (sigma / 1.4427)).to(torch.bfloat16)
+        count.zero_()
+        B.hero_attention(q, k, vt, o, n, cfg.n_heads, cfg.head_dim, scratch, count)      # warm-up, and the count
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(3):
+            B.hero_attention(q, k, vt, o, n, cfg.n_heads, cfg.head_dim, scratch, count)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 3
+        legs.append({"score_sigma_log2": sigma, "ms": round(ms, 4), "tflops": round(4.0 * r * n * d / ms / 1e9, 1),
+                     "fallback_workgroups": int(count.item()) // 4, "workgroups": n_wg})
+    return legs
 
 
 def main():
@@ -145,7 +243,7 @@ def main():
     cache.hero_cache_reset()
     torch.cuda.synchronize()
 
-    K = args.steps
+    K = args.steps if args.steps is not None else (cfg.n_steps if cfg.n_steps >= 10 else 50)
 
     def kernel_table(prof):
         table = {}
@@ -206,11 +304,15 @@ def main():
     dominant = max(kernels, key=lambda k: kernels[k]["total_ms"])
     dk = kernels[dominant]
     mfma = dk["unit"] == "TFLOP/s"
+    # HBM traffic of the dominant kernel from the stored counter profile, if that profile was taken
+    # with these kernel sources (else null: the counters are of another build)
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
         with open(tpath) as f:
-            traffic = json.load(f).get(args.workload, {}).get(dominant)
+            stored = json.load(f)
+        if stored.get("_kernel_sources_sha") == kernel_sources_sha():
+            traffic = stored.get(args.workload, {}).get(dominant)
     roofline = {"kernel": dominant, "bound": "mfma" if mfma else "hbm", "achieved": dk["achieved"],
                 "peak": PEAK_BF16_TFLOPS if mfma else PEAK_HBM_GBS, "unit": dk["unit"], "frac": dk["frac"],
                 "avg_launch_ms": dk["avg_ms"], "launches": dk["launches"], "traffic": traffic}
@@ -228,11 +330,16 @@ def main():
         "cached_step_ms": round(mean(cached_ms), 3) if cached_ms else None,
         "speedup_vs_all_full": round(mean(full_ms) / ms_per_step, 3) if full_ms else None,
         "roofline": roofline,
+        "targets": {name: {"frac": kernels[name]["frac"], "target": tgt, "met": kernels[name]["frac"] >= tgt}
+                    for name, tgt in TARGETS.items() if name in kernels},
+        "attention_fallback_workgroups": int(cache.hero_cache_view(0, B.VIEW_FALLBACKS).item()),
         "kernels": kernels,
         "kernels_note": "entries of the dominant kind: HIP events inside the timed region; all others: an untimed "
                         "pass over the same steps with every launch bracketed",
         "paper_context": "paper reports 1.73x (FLOPs ratio; 1.68x by latency) on A100-80G, Aether, M=2, K=20, R=0.2",
     }
+    if args.score_scale and cfg.head_dim == 64:
+        out["attention_score_scale"] = attention_fallback_legs(cfg, torch, B)
     if not args.no_cpu_baseline:
         w0 = {k: v.float().cpu().numpy() for k, v in weights[0].items()}
         out["cpu_baseline"] = cpu_baseline(cfg, w0, x0.float().cpu().numpy(), args.cpu_sample_rows, K)

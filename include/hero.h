@@ -64,6 +64,17 @@ enum { HERO_SELECT_AGE_PRIORITY = 0, HERO_SELECT_AGE_WEIGHTED = 1 };
  *         with x; pair i of an axis with n pairs turns by pos * 10000^(-i/n).  Text rows and V are
  *         not rotated.  Order: projection, QKNORM, ROPE, softmax scale. */
 enum { HERO_BLOCK_ADALN = 1, HERO_BLOCK_QKNORM = 2, HERO_BLOCK_ROPE = 4 };
+/* Extra caches, so that the per-layer calls can be used across the K boundary of Alg. 1 (the step
+ * schedule of hero_step is not affected):
+ * KV_ALL_LAYERS:   every layer keeps K / V^T, so hero_refresh_layer works on any layer (with
+ *                  n_sel = 0 on every layer this is plain feature reuse, as FoRA does);
+ * PREV_ALL_LAYERS: every layer keeps the previous full step's S, so hero_extrapolate_layer works
+ *                  on any layer (first-order forecasting on every layer without setting K = 0). */
+enum { HERO_CACHE_KV_ALL_LAYERS = 1, HERO_CACHE_PREV_ALL_LAYERS = 2 };
+/* CHECK_IDX: hero_refresh_layer first verifies on the device that dev_idx holds n_sel distinct rows
+ * in [0, N) and returns HERO_ERR_INVALID_ARG, launching nothing else, if it does not.  The check
+ * reads its verdict back, i.e. it synchronises the stream: a debugging aid, not for timed runs. */
+enum { HERO_DEBUG_CHECK_IDX = 1 };
 
 /* Plain-data configuration, copied at hero_cache_create(). */
 typedef struct hero_config {
@@ -82,7 +93,9 @@ typedef struct hero_config {
   float   ln_eps;
   uint64_t seed;       /* selection seed                                                 */
   int32_t select_mode; /* HERO_SELECT_AGE_PRIORITY or HERO_SELECT_AGE_WEIGHTED (Sec. 3.3 tracking) */
-  int32_t block_flags; /* 0: the plain block of Eq. 2; or a sum of HERO_BLOCK_* (see below)        */
+  int32_t block_flags; /* 0: the plain block of Eq. 2; or a sum of HERO_BLOCK_* (see above)        */
+  int32_t cache_flags; /* 0, or a sum of HERO_CACHE_*: caches beyond those Alg. 1 needs              */
+  int32_t debug_flags; /* 0, or HERO_DEBUG_CHECK_IDX                                                 */
 } hero_config;
 
 /* Borrowed device pointers to one block's parameters (bf16). */
@@ -132,8 +145,11 @@ int hero_cache_reset(hero_cache_t c, void* stream);
 int hero_set_layer_weights(hero_cache_t c, int32_t layer, const hero_layer_weights* w);
 
 /* Alg. 1 "Initial Caching" for one layer (Eq. 2 on all N rows): x <- block(x),
- * cache S = G_attn + G_ffn for all rows, K/V for shallow layers; deep layers
- * first move the current S to the previous generation. */
+ * cache S = G_attn + G_ffn for all rows, K/V for shallow layers; deep layers keep the
+ * S they held as the previous generation (the new one is written beside it and the two
+ * change places once every launch has been accepted).  If a launch fails part-way the
+ * layer is left with at most one valid generation: a shallow layer counts as never filled,
+ * a deep layer keeps its current S and loses its previous one. */
 int hero_full_layer(hero_cache_t c, int32_t layer, void* dev_x, void* stream);
 
 /* S(z) of Eq. 4 with frequency-aware tracking (Sec. 3.3): writes n_sel row
@@ -148,13 +164,17 @@ int hero_reset_ages(hero_cache_t c, void* stream);
 /* Eq. 3 / Alg. 1 (l < K): recompute QKV, attention against the full cached K/V,
  * and FFN for the n_sel rows in dev_idx (unique, in [0, N)), scatter the
  * results into the caches, then x += S on all N rows.  n_sel = 0 is pure reuse.
- * Errors: STATE if the layer has not been filled, INVALID_ARG if layer >= K. */
+ * dev_idx must hold distinct rows in [0, N): a row listed twice is a write race, a row out of range
+ * an out-of-bounds write; with HERO_DEBUG_CHECK_IDX the call verifies this first.
+ * Errors: STATE if the layer has not been filled; INVALID_ARG if the layer keeps no K/V
+ * (layer >= K without HERO_CACHE_KV_ALL_LAYERS), or if the index check fails. */
 int hero_refresh_layer(hero_cache_t c, int32_t layer, void* dev_x, const int32_t* dev_idx,
                        int32_t n_sel, void* stream);
 
 /* Eq. 5 / Alg. 1 (l >= K): x += S_t + (S_t - S_{t+M}) * k / M on all rows; the
  * difference is taken as zero while only one full-step generation exists.
- * 0 <= k <= M.  Errors: STATE if not filled, INVALID_ARG if layer < K. */
+ * 0 <= k <= M.  Errors: STATE if not filled; INVALID_ARG if the layer keeps no previous
+ * generation (layer < K without HERO_CACHE_PREV_ALL_LAYERS). */
 int hero_extrapolate_layer(hero_cache_t c, int32_t layer, void* dev_x, int32_t k, void* stream);
 
 /* Alg. 1 for one denoising step: full step if step % M == 0 (every layer via
@@ -179,6 +199,9 @@ int hero_step(hero_cache_t c, void* dev_x, int32_t step, void* stream);
 /* Read-only views into the handle, for tests and tools.  `what`:
  *   0 S_cur [N,hidden]   1 S_prev [N,hidden] (deep)   2 K [N,hidden] (shallow)
  *   3 V^T [hidden,N_pad] (shallow)   4 ages int32 [n_video]   5 last idx int32 [n_sel]
+ *   6 uint32 [1]: attention workgroups (256 queries of one head) that, since create / reset, found
+ *     a row sum outside the range of the maximum-free softmax and recomputed their block with the
+ *     running-maximum form (see hero_attention_counted); 0 for activations of ordinary scale
  * Returns the device pointer and the leading dimension in elements. */
 int hero_cache_view(hero_cache_t c, int32_t layer, int32_t what, void** dev_ptr, int64_t* ld);
 
@@ -235,6 +258,17 @@ int hero_linear(const void* dev_a, const void* dev_w, const void* dev_bias, void
 int hero_linear_scratch(const void* dev_a, const void* dev_w, const void* dev_bias, void* dev_c,
                         int32_t m, int32_t n, int32_t k, int32_t act, void* dev_scratch,
                         size_t scratch_bytes, void* stream);
+
+/* The same, and *dev_fallbacks (device uint32, optional) += the number of workgroups (256 queries of
+ * one head) that took the slower way out.  head_dim 64 evaluates softmax as 2^(q.k log2(e)/sqrt(head_dim))
+ * without a running maximum, which is exact while every row sum stays within [2^-80, 2^80]; a workgroup
+ * in which some row sum leaves that range recomputes its 256 queries with the running-maximum form
+ * (the result is the plain definition's either way; the cost of such a block roughly triples).
+ * With scores of a few units, as LayerNorm-ed activations give, that never happens; it takes
+ * |q.k| / sqrt(head_dim) beyond about 50. */
+int hero_attention_counted(const void* dev_q, const void* dev_k, const void* dev_vt, int64_t ld_vt,
+                           void* dev_o, int32_t r, int32_t n_keys, int32_t n_heads, int32_t head_dim,
+                           void* dev_scratch, size_t scratch_bytes, uint32_t* dev_fallbacks, void* stream);
 
 /* For callers that cannot allocate device memory or pass a workspace (code under HIP graph capture,
  * tight serving loops, harnesses that forbid hipMalloc): hero_linear_scratch with the partial sums

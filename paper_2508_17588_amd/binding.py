@@ -25,7 +25,7 @@ HERO_ERR_HIP = 5
 DTYPE_BF16 = 0
 DTYPE_FP32 = 1
 
-VIEW_S_CUR, VIEW_S_PREV, VIEW_K, VIEW_VT, VIEW_AGES, VIEW_IDX = range(6)
+VIEW_S_CUR, VIEW_S_PREV, VIEW_K, VIEW_VT, VIEW_AGES, VIEW_IDX, VIEW_FALLBACKS = range(7)
 
 PROF_KINDS = ("select", "ln", "gemm_qkv", "attention", "gemm_o", "gemm_ff1", "gemm_ff2", "resid", "extrap", "deepsum", "qk_post")
 
@@ -33,13 +33,15 @@ WEIGHT_FIELDS = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
                  "ln2_g", "ln2_b", "w_ff1", "b_ff1", "w_ff2", "b_ff2")
 EXTRA_WEIGHT_FIELDS = ("q_norm_g", "q_norm_b", "k_norm_g", "k_norm_b", "mod")
 BLOCK_ADALN, BLOCK_QKNORM, BLOCK_ROPE = 1, 2, 4
+CACHE_KV_ALL_LAYERS, CACHE_PREV_ALL_LAYERS = 1, 2
+DEBUG_CHECK_IDX = 1
 
 EXPORTS = (
     "hero_last_error", "hero_num_selected", "hero_cache_bytes", "hero_cache_create",
     "hero_cache_destroy", "hero_cache_reset", "hero_set_layer_weights", "hero_full_layer",
     "hero_select", "hero_reset_ages", "hero_refresh_layer", "hero_extrapolate_layer", "hero_step",
     "hero_cache_view", "hero_cache_state", "hero_profile_begin", "hero_profile_begin_kinds", "hero_profile_end", "hero_gather_ln", "hero_linear", "hero_linear_scratch", "hero_linear_static",
-    "hero_attention", "hero_attention_scratch",
+    "hero_attention", "hero_attention_scratch", "hero_attention_counted",
     "hero_axpy_features", "hero_second_diff_stats", "hero_stability_scores",
 )
 
@@ -56,7 +58,8 @@ class hero_config(Structure):
                 ("frames", c_int32), ("height", c_int32), ("width", c_int32), ("n_text", c_int32),
                 ("patch_h", c_int32), ("patch_w", c_int32), ("ratio", c_float),
                 ("resid_dtype", c_int32), ("ln_eps", c_float), ("seed", c_uint64),
-                ("select_mode", c_int32), ("block_flags", c_int32)]
+                ("select_mode", c_int32), ("block_flags", c_int32),
+                ("cache_flags", c_int32), ("debug_flags", c_int32)]
 
 
 class hero_layer_weights(Structure):
@@ -102,6 +105,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
         "hero_linear_static": [P, P, P, P, I, I, I, I, P],
         "hero_attention": [P, P, P, c_int64, P, I, I, I, I, P],
         "hero_attention_scratch": [P, P, P, c_int64, P, I, I, I, I, P, ctypes.c_size_t, P],
+        "hero_attention_counted": [P, P, P, c_int64, P, I, I, I, I, P, ctypes.c_size_t, P, P],
         "hero_axpy_features": [P, I, P, P, c_float, c_int64, P],
         "hero_second_diff_stats": [P, P, P, c_int64, P, ctypes.c_size_t, P, I, P],
         "hero_stability_scores": [POINTER(ctypes.c_double), I, POINTER(ctypes.c_double)],
@@ -126,7 +130,8 @@ def make_config(cfg, resid_fp32: Optional[bool] = None) -> hero_config:
     return hero_config(cfg.n_layers, cfg.n_shallow, cfg.interval, cfg.hidden, cfg.n_heads, cfg.head_dim,
                        cfg.ffn_dim, cfg.frames, cfg.height, cfg.width, cfg.n_text, cfg.patch_h, cfg.patch_w,
                        cfg.ratio, DTYPE_FP32 if rf else DTYPE_BF16, cfg.ln_eps, cfg.seed,
-                       getattr(cfg, "select_mode", 0), getattr(cfg, "block_flags", 0))
+                       getattr(cfg, "select_mode", 0), getattr(cfg, "block_flags", 0),
+                       getattr(cfg, "cache_flags", 0), getattr(cfg, "debug_flags", 0))
 
 
 def _stream() -> c_void_p:
@@ -277,7 +282,7 @@ class HeroCache:
         p, ld = c_void_p(0), c_int64(0)
         _check(self.lib.hero_cache_view(self.handle, layer, what, byref(p), byref(ld)))
         cfg = self.cfg
-        if what in (VIEW_AGES, VIEW_IDX):
+        if what in (VIEW_AGES, VIEW_IDX, VIEW_FALLBACKS):
             base, dtype, shape, esz = self.cache_buf if what == VIEW_AGES else self.ws_buf, torch.int32, (ld.value,), 4
         elif what == VIEW_VT:
             base, dtype, shape, esz = self.cache_buf, torch.bfloat16, (cfg.hidden, ld.value), 2
@@ -342,8 +347,10 @@ def hero_linear_static(a, w, bias, c, act: int = 0):
     _check(load_library().hero_linear_static(_ptr(a), _ptr(w), _ptr(bias), _ptr(c), m, n, k, act, _stream()))
 
 
-def hero_attention(q, k, vt, o, n_keys: int, n_heads: int, head_dim: int, scratch=None):
-    """scratch: optional contiguous device tensor; with it the call goes through hero_attention_scratch."""
+def hero_attention(q, k, vt, o, n_keys: int, n_heads: int, head_dim: int, scratch=None, fallbacks=None):
+    """scratch: optional contiguous device tensor; with it the call goes through hero_attention_scratch.
+    fallbacks: optional int32 device tensor of one element; the call then goes through
+    hero_attention_counted and adds the number of workgroups that took the running-maximum path."""
     import torch
     for t, n in ((q, "q"), (k, "k"), (vt, "vt"), (o, "o")):
         _need(t, torch.bfloat16, n)
@@ -351,6 +358,13 @@ def hero_attention(q, k, vt, o, n_keys: int, n_heads: int, head_dim: int, scratc
     d = n_heads * head_dim
     if q.shape[1] != d or k.shape[1] != d or k.shape[0] < n_keys or vt.shape[0] != d or o.numel() < r * d:
         raise ValueError("shape mismatch")
+    if fallbacks is not None:
+        _need(fallbacks, torch.int32, "fallbacks")
+        _check(load_library().hero_attention_counted(_ptr(q), _ptr(k), _ptr(vt), vt.shape[1], _ptr(o), r, n_keys,
+                                                     n_heads, head_dim, _ptr(scratch),
+                                                     0 if scratch is None else scratch.numel() * scratch.element_size(),
+                                                     _ptr(fallbacks), _stream()))
+        return
     if scratch is not None:
         _check(load_library().hero_attention_scratch(_ptr(q), _ptr(k), _ptr(vt), vt.shape[1], _ptr(o), r, n_keys,
                                                      n_heads, head_dim, _ptr(scratch),

@@ -621,6 +621,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_hd64_kernel(AttnArgs a, 
   // were the scores inside the range of the reference-free form?
   const int bad = !(l[0] >= 0x1p-80f && l[0] <= 0x1p80f) | !(l[1] >= 0x1p-80f && l[1] <= 0x1p80f);
   if (__syncthreads_or(bad)) {
+    if (tid_after == 0 && a.fallback_count != nullptr) atomicAdd(a.fallback_count, 1u);
     attention_general<HD, NW>(a, head, q0, a.q_scale, &sK[0][0], &sV[0][0]);
     return;
   }
@@ -662,6 +663,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_hd64_fixup_kernel(AttnAr
   }
   const int bad = !(l[0] >= 0x1p-80f && l[0] <= 0x1p80f) | !(l[1] >= 0x1p-80f && l[1] <= 0x1p80f);
   if (__syncthreads_or(bad)) {
+    if (tid == 0 && a.fallback_count != nullptr) atomicAdd(a.fallback_count, 1u);
     attention_general<HD, NW>(a, head, q0, a.q_scale, &skv[0][0][0], &skv[1][0][0]);
     return;
   }

@@ -113,6 +113,10 @@ int check_config(const hero_config* c) {
     return fail(HERO_ERR_SHAPE, "age-weighted selection needs patches of at most 65535 tokens");
   if (c->block_flags < 0 || c->block_flags > (HERO_BLOCK_ADALN | HERO_BLOCK_QKNORM | HERO_BLOCK_ROPE))
     return fail(HERO_ERR_INVALID_ARG, "block_flags must be a sum of HERO_BLOCK_* values");
+  if (c->cache_flags < 0 || c->cache_flags > (HERO_CACHE_KV_ALL_LAYERS | HERO_CACHE_PREV_ALL_LAYERS))
+    return fail(HERO_ERR_INVALID_ARG, "cache_flags must be a sum of HERO_CACHE_* values");
+  if (c->debug_flags < 0 || c->debug_flags > HERO_DEBUG_CHECK_IDX)
+    return fail(HERO_ERR_INVALID_ARG, "debug_flags must be 0 or HERO_DEBUG_CHECK_IDX");
   if ((c->block_flags & HERO_BLOCK_ROPE) && c->head_dim % 16 != 0)
     return fail(HERO_ERR_SHAPE, "rotary positions need head_dim to be a multiple of 16");
   if (c->head_dim != 32 && c->head_dim != 64) return fail(HERO_ERR_SHAPE, "head_dim must be 32 or 64");
@@ -157,13 +161,21 @@ SelectGeom make_geom(const hero_config& c) {
 struct Layout {
   int64_t n_tokens, n_video, n_pad;
   size_t ages_off;
-  size_t layer_stride_shallow, layer_stride_deep;
+  bool kv_all, prev_all;         // HERO_CACHE_*: K/V^T on deep layers too, S_prev on shallow layers too
   size_t s_bytes, k_bytes, vt_bytes;
   size_t t_off[2], t_bytes;      // fp32 sums of the deep layers' features (two generations); 0 bytes if < 2 deep layers
   size_t rope_off, rope_bytes;   // (cos, sin) of every video token's rotation angles; 0 bytes without HERO_BLOCK_ROPE
   size_t cache_bytes;
   // workspace
   size_t idx_off, a_off, q_off, o_off, f_off, ktmp_off, vtmp_off, splitk_off, splitk_bytes, ws_bytes;
+  size_t seen_off, seen_bytes;   // index check: one bit per token, then one verdict word
+  size_t stat_off;               // counters (word 0: attention workgroups that took the running-maximum path)
+  // bytes of one layer's slabs: S_cur, then K and V^T if it keeps them, then S_prev if it keeps one
+  bool keeps_kv(const hero_config& c, int l) const { return l < c.n_shallow || kv_all; }
+  bool keeps_prev(const hero_config& c, int l) const { return l >= c.n_shallow || prev_all; }
+  size_t layer_bytes(const hero_config& c, int l) const {
+    return s_bytes + (keeps_kv(c, l) ? k_bytes + vt_bytes : 0) + (keeps_prev(c, l) ? s_bytes : 0);
+  }
 };
 
 Layout make_layout(const hero_config& c) {
@@ -176,9 +188,9 @@ Layout make_layout(const hero_config& c) {
   L.vt_bytes = align_up((size_t)c.hidden * L.n_pad * 2, 256);
   L.ages_off = 0;
   size_t off = align_up((size_t)L.n_video * 4, 256);
-  L.layer_stride_shallow = L.s_bytes + L.k_bytes + L.vt_bytes;
-  L.layer_stride_deep = 2 * L.s_bytes;
-  off += (size_t)c.n_shallow * L.layer_stride_shallow + (size_t)(c.n_layers - c.n_shallow) * L.layer_stride_deep;
+  L.kv_all = (c.cache_flags & HERO_CACHE_KV_ALL_LAYERS) != 0;
+  L.prev_all = (c.cache_flags & HERO_CACHE_PREV_ALL_LAYERS) != 0;
+  for (int l = 0; l < c.n_layers; ++l) off += L.layer_bytes(c, l);
   L.t_bytes = (c.n_layers - c.n_shallow >= 2) ? align_up((size_t)L.n_tokens * c.hidden * 4, 256) : 0;
   L.t_off[0] = off; off += L.t_bytes;
   L.t_off[1] = off; off += L.t_bytes;
@@ -192,7 +204,7 @@ Layout make_layout(const hero_config& c) {
   L.o_off = w; w += L.s_bytes;
   L.f_off = w; w += align_up((size_t)L.n_tokens * c.ffn_dim * 2, 256);
   L.ktmp_off = w; L.vtmp_off = w;
-  if (c.n_shallow < c.n_layers) {
+  if (c.n_shallow < c.n_layers && !L.kv_all) {       // transient K / V^T of a deep layer's full step
     w += L.k_bytes;
     L.vtmp_off = w;
     w += L.vt_bytes;
@@ -201,6 +213,11 @@ Layout make_layout(const hero_config& c) {
   L.splitk_off = w;
   L.splitk_bytes = L.n_tokens >= 2048 ? (size_t)512 * 262144 : 0;
   w += L.splitk_bytes;
+  L.seen_off = w;
+  L.seen_bytes = align_up(((size_t)L.n_tokens + 31) / 32 * 4 + 4, 256);
+  w += L.seen_bytes;
+  L.stat_off = w;
+  w += 256;
   L.ws_bytes = w;
   return L;
 }
@@ -228,9 +245,9 @@ struct Profiler {
 
 struct LayerState {
   bf16_t* s_cur = nullptr;
-  bf16_t* s_prev = nullptr;   // deep only
-  bf16_t* k = nullptr;        // shallow only
-  bf16_t* vt = nullptr;       // shallow only
+  bf16_t* s_prev = nullptr;   // deep layers (every layer with HERO_CACHE_PREV_ALL_LAYERS)
+  bf16_t* k = nullptr;        // shallow layers (every layer with HERO_CACHE_KV_ALL_LAYERS)
+  bf16_t* vt = nullptr;
   int fills = 0;
   bool has_weights = false;
   hero_layer_weights w;
@@ -248,6 +265,8 @@ struct hero_cache {
   int32_t* idx = nullptr;
   bf16_t *a = nullptr, *q = nullptr, *o = nullptr, *f = nullptr, *ktmp = nullptr, *vtmp = nullptr;
   float* splitk = nullptr;        // GEMM k-split partial sums (nullptr when the problem is too small to need them)
+  uint32_t* seen = nullptr;       // index check: token bitmap followed by the verdict word
+  uint32_t* stats = nullptr;      // word 0: attention fallback workgroups since create / reset
   float2* rope = nullptr;         // rotation table (nullptr without HERO_BLOCK_ROPE)
   std::vector<LayerState> layers;
   // deep-stack sums: slot i holds sum_l S_cur^l taken when the deep layers' fill counts were
@@ -347,6 +366,7 @@ int run_block_rows(hero_cache_t c, LayerState& ls, void* x, const int32_t* rows,
   at.r = n_rows; at.n_keys = (int)c->lay.n_tokens; at.n_heads = cfg.n_heads; at.head_dim = cfg.head_dim;
   at.q_scale = 1.0f;
   at.split_ws = c->splitk; at.split_ws_bytes = c->lay.splitk_bytes;    // shared with the GEMMs: same stream, never concurrent
+  at.fallback_count = c->stats;
   PROF_LAUNCH(c, HERO_PROF_ATTN, 4.0 * rd * n_all, st, launch_attention(at, st));
 
   memset(&g, 0, sizeof(g));
@@ -555,21 +575,22 @@ int hero_cache_create(const hero_config* cfg, void* dev_cache, size_t cache_byte
   c->ktmp = (bf16_t*)(c->ws + L.ktmp_off);
   c->vtmp = (bf16_t*)(c->ws + L.vtmp_off);
   c->splitk = L.splitk_bytes ? (float*)(c->ws + L.splitk_off) : nullptr;
+  c->seen = (uint32_t*)(c->ws + L.seen_off);
+  c->stats = (uint32_t*)(c->ws + L.stat_off);
   c->layers.resize(cfg->n_layers);
   if (L.t_bytes) { c->t[0] = (float*)(c->cache + L.t_off[0]); c->t[1] = (float*)(c->cache + L.t_off[1]); }
   if (L.rope_bytes) c->rope = (float2*)(c->cache + L.rope_off);
   size_t off = align_up((size_t)L.n_video * 4, 256);
   for (int l = 0; l < cfg->n_layers; ++l) {
     LayerState& ls = c->layers[l];
-    ls.s_cur = (bf16_t*)(c->cache + off);
-    if (l < cfg->n_shallow) {
-      ls.k = (bf16_t*)(c->cache + off + L.s_bytes);
-      ls.vt = (bf16_t*)(c->cache + off + L.s_bytes + L.k_bytes);
-      off += L.layer_stride_shallow;
-    } else {
-      ls.s_prev = (bf16_t*)(c->cache + off + L.s_bytes);
-      off += L.layer_stride_deep;
+    size_t o = off;
+    ls.s_cur = (bf16_t*)(c->cache + o); o += L.s_bytes;
+    if (L.keeps_kv(*cfg, l)) {
+      ls.k = (bf16_t*)(c->cache + o); o += L.k_bytes;
+      ls.vt = (bf16_t*)(c->cache + o); o += L.vt_bytes;
     }
+    if (L.keeps_prev(*cfg, l)) { ls.s_prev = (bf16_t*)(c->cache + o); o += L.s_bytes; }
+    off += L.layer_bytes(*cfg, l);
   }
   hipStream_t st = (hipStream_t)stream;
   hipError_t e = hipMemsetAsync(dev_cache, 0, L.cache_bytes, st);
@@ -603,6 +624,7 @@ int hero_cache_reset(hero_cache_t c, void* stream) {
   c->n_full = 0;
   c->last_full = -1;
   c->last_n_sel = 0;
+  HIP_TRY(launch_fill_i32(reinterpret_cast<int32_t*>(c->stats), 0, 1, (hipStream_t)stream));
   return hero_reset_ages(c, stream);
 }
 
@@ -632,24 +654,32 @@ int hero_full_layer(hero_cache_t c, int32_t layer, void* dev_x, void* stream) {
   LayerState& ls = c->layers[layer];
   if (!ls.has_weights) return fail(HERO_ERR_STATE, "layer %d has no weights", layer);
   hipStream_t st = (hipStream_t)stream;
-  const bool shallow = layer < c->cfg.n_shallow;
-  if (!shallow && ls.fills > 0) std::swap(ls.s_cur, ls.s_prev);   // G_{t+M} <- G_t (Sec. 3.4)
-  bf16_t* k_dst = shallow ? ls.k : c->ktmp;
-  bf16_t* vt_dst = shallow ? ls.vt : c->vtmp;
+  // A layer that keeps two generations writes the new one over the older (G_{t+M} <- G_t, Sec. 3.4)
+  // and the two change places only once every launch has been accepted.
+  const bool rotate = ls.s_prev != nullptr && ls.fills > 0;
+  bf16_t* s_dst = rotate ? ls.s_prev : ls.s_cur;
+  bf16_t* k_dst = ls.k ? ls.k : c->ktmp;
+  bf16_t* vt_dst = ls.vt ? ls.vt : c->vtmp;
   c->in_full = true;
   bool resid_done = false;
-  rc = run_block_rows(c, ls, dev_x, nullptr, (int)c->lay.n_tokens, k_dst, vt_dst, ls.s_cur, st, &resid_done);
-  if (rc) { c->in_full = false; return rc; }
+  rc = run_block_rows(c, ls, dev_x, nullptr, (int)c->lay.n_tokens, k_dst, vt_dst, s_dst, st, &resid_done);
   const bool x_fp32 = c->cfg.resid_dtype == HERO_DTYPE_FP32;
   const double nd = (double)c->lay.n_tokens * c->cfg.hidden;
-  rc = [&]() -> int {
-    if (resid_done) return HERO_OK;
-    PROF_LAUNCH(c, HERO_PROF_RESID, nd * (x_fp32 ? 10.0 : 6.0), st,
-                launch_axpy_features(dev_x, x_fp32, ls.s_cur, nullptr, 0.f, c->lay.n_tokens * c->cfg.hidden, st));
-    return HERO_OK;
-  }();
+  if (rc == HERO_OK)
+    rc = [&]() -> int {
+      if (resid_done) return HERO_OK;
+      PROF_LAUNCH(c, HERO_PROF_RESID, nd * (x_fp32 ? 10.0 : 6.0), st,
+                  launch_axpy_features(dev_x, x_fp32, s_dst, nullptr, 0.f, c->lay.n_tokens * c->cfg.hidden, st));
+      return HERO_OK;
+    }();
   c->in_full = false;
-  if (rc) return rc;
+  if (rc) {
+    // the slab written to may hold part of a new generation: what it held before is gone
+    ls.fills = rotate ? 1 : 0;
+    c->t_key[0].clear(); c->t_key[1].clear();      // and no sum over the deep layers is current any more
+    return rc;
+  }
+  if (rotate) std::swap(ls.s_cur, ls.s_prev);
   ls.fills += 1;
   return HERO_OK;
 }
@@ -673,15 +703,26 @@ int hero_refresh_layer(hero_cache_t c, int32_t layer, void* dev_x, const int32_t
   int rc = check_layer(c, layer);
   if (rc) return rc;
   if (!dev_x) return fail(HERO_ERR_INVALID_ARG, "x is null");
-  if (layer >= c->cfg.n_shallow)
-    return fail(HERO_ERR_INVALID_ARG, "layer %d is a deep layer (n_shallow = %d): it keeps no K/V cache", layer,
-                c->cfg.n_shallow);
+  LayerState& ls = c->layers[layer];
+  if (ls.k == nullptr)
+    return fail(HERO_ERR_INVALID_ARG, "layer %d is a deep layer (n_shallow = %d) and keeps no K/V cache "
+                "(configure HERO_CACHE_KV_ALL_LAYERS to refresh it)", layer, c->cfg.n_shallow);
   if (n_sel < 0 || n_sel > c->lay.n_tokens) return fail(HERO_ERR_INVALID_ARG, "n_sel %d out of range", n_sel);
   if (n_sel > 0 && !dev_idx) return fail(HERO_ERR_INVALID_ARG, "dev_idx is null");
-  LayerState& ls = c->layers[layer];
   if (!ls.has_weights) return fail(HERO_ERR_STATE, "layer %d has no weights", layer);
   if (ls.fills == 0) return fail(HERO_ERR_STATE, "layer %d refreshed before a full step filled its cache", layer);
   hipStream_t st = (hipStream_t)stream;
+  if ((c->cfg.debug_flags & HERO_DEBUG_CHECK_IDX) && n_sel > 0) {
+    // before anything is scattered: are the listed rows distinct and inside [0, N)?
+    const int n_tok = (int)c->lay.n_tokens;
+    HIP_TRY(launch_check_idx(dev_idx, n_sel, n_tok, c->seen, st));
+    uint32_t verdict = 0;
+    HIP_TRY(hipMemcpyAsync(&verdict, c->seen + (n_tok + 31) / 32, sizeof(verdict), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    if (verdict != 0)
+      return fail(HERO_ERR_INVALID_ARG, "dev_idx holds %s%s%s", (verdict & 1) ? "a row outside [0, N)" : "",
+                  verdict == 3 ? " and " : "", (verdict & 2) ? "a row listed twice" : "");
+  }
   if (n_sel > 0) {
     rc = run_block_rows(c, ls, dev_x, dev_idx, n_sel, ls.k, ls.vt, ls.s_cur, st);
     if (rc) return rc;
@@ -697,11 +738,11 @@ int hero_extrapolate_layer(hero_cache_t c, int32_t layer, void* dev_x, int32_t k
   int rc = check_layer(c, layer);
   if (rc) return rc;
   if (!dev_x) return fail(HERO_ERR_INVALID_ARG, "x is null");
-  if (layer < c->cfg.n_shallow)
-    return fail(HERO_ERR_INVALID_ARG, "layer %d is a shallow layer (n_shallow = %d): it keeps one generation", layer,
-                c->cfg.n_shallow);
-  if (k < 0 || k > c->cfg.interval) return fail(HERO_ERR_INVALID_ARG, "k = %d outside [0, %d]", k, c->cfg.interval);
   LayerState& ls = c->layers[layer];
+  if (ls.s_prev == nullptr)
+    return fail(HERO_ERR_INVALID_ARG, "layer %d is a shallow layer (n_shallow = %d) and keeps one generation "
+                "(configure HERO_CACHE_PREV_ALL_LAYERS to extrapolate it)", layer, c->cfg.n_shallow);
+  if (k < 0 || k > c->cfg.interval) return fail(HERO_ERR_INVALID_ARG, "k = %d outside [0, %d]", k, c->cfg.interval);
   if (ls.fills == 0) return fail(HERO_ERR_STATE, "layer %d extrapolated before a full step filled its cache", layer);
   const bf16_t* prev = ls.fills >= 2 ? ls.s_prev : nullptr;
   float alpha = (float)k / (float)c->cfg.interval;
@@ -722,7 +763,13 @@ int hero_step(hero_cache_t c, void* dev_x, int32_t step, void* stream) {
   int rc;
   if (step % cfg.interval == 0) {
     for (int l = 0; l < cfg.n_layers; ++l)
-      if ((rc = hero_full_layer(c, l, dev_x, stream)) != HERO_OK) return rc;
+      if ((rc = hero_full_layer(c, l, dev_x, stream)) != HERO_OK) {
+        // layers before l hold the new generation, the others the old one: no cached step until a
+        // full step has gone through
+        c->n_full = 0;
+        c->last_full = -1;
+        return rc;
+      }
     if ((rc = hero_reset_ages(c, stream)) != HERO_OK) return rc;
     c->n_full += 1;
     c->last_full = step;
@@ -759,6 +806,7 @@ int hero_cache_view(hero_cache_t c, int32_t layer, int32_t what, void** dev_ptr,
   if (!dev_ptr || !ld) return fail(HERO_ERR_INVALID_ARG, "output pointer is null");
   if (what == 4) { *dev_ptr = c->ages; *ld = c->lay.n_video; return HERO_OK; }
   if (what == 5) { *dev_ptr = c->idx; *ld = c->last_n_sel; return HERO_OK; }
+  if (what == 6) { *dev_ptr = c->stats; *ld = 1; return HERO_OK; }
   int rc = check_layer(c, layer);
   if (rc) return rc;
   LayerState& ls = c->layers[layer];
@@ -881,9 +929,9 @@ int hero_linear_static(const void* dev_a, const void* dev_w, const void* dev_bia
   return hero_linear_scratch(dev_a, dev_w, dev_bias, dev_c, m, n, k, act, ws, STATIC_SCRATCH_BYTES, stream);
 }
 
-int hero_attention_scratch(const void* dev_q, const void* dev_k, const void* dev_vt, int64_t ld_vt, void* dev_o,
+int hero_attention_counted(const void* dev_q, const void* dev_k, const void* dev_vt, int64_t ld_vt, void* dev_o,
                            int32_t r, int32_t n_keys, int32_t n_heads, int32_t head_dim, void* dev_scratch,
-                           size_t scratch_bytes, void* stream) {
+                           size_t scratch_bytes, uint32_t* dev_fallbacks, void* stream) {
   if (!dev_k || !dev_vt || (r > 0 && (!dev_q || !dev_o))) return fail(HERO_ERR_INVALID_ARG, "null pointer");
   if (r < 0 || n_keys < 1 || n_heads < 1) return fail(HERO_ERR_INVALID_ARG, "bad sizes");
   if (head_dim != 32 && head_dim != 64) return fail(HERO_ERR_SHAPE, "head_dim must be 32 or 64");
@@ -896,9 +944,18 @@ int hero_attention_scratch(const void* dev_q, const void* dev_k, const void* dev
   a.q_scale = 1.4426950408889634f / sqrtf((float)head_dim);
   if (!aligned16({dev_q, dev_k, dev_vt, dev_o, dev_scratch}))
     return fail(HERO_ERR_INVALID_ARG, "q, k, vt, o and scratch must be 16-byte aligned");
+  if ((uintptr_t)dev_fallbacks & 3) return fail(HERO_ERR_INVALID_ARG, "the fallback counter must be 4-byte aligned");
   a.split_ws = (float*)dev_scratch; a.split_ws_bytes = dev_scratch ? scratch_bytes : 0;
+  a.fallback_count = dev_fallbacks;
   HIP_TRY(launch_attention(a, (hipStream_t)stream));
   return HERO_OK;
+}
+
+int hero_attention_scratch(const void* dev_q, const void* dev_k, const void* dev_vt, int64_t ld_vt, void* dev_o,
+                           int32_t r, int32_t n_keys, int32_t n_heads, int32_t head_dim, void* dev_scratch,
+                           size_t scratch_bytes, void* stream) {
+  return hero_attention_counted(dev_q, dev_k, dev_vt, ld_vt, dev_o, r, n_keys, n_heads, head_dim, dev_scratch,
+                                scratch_bytes, nullptr, stream);
 }
 
 int hero_attention(const void* dev_q, const void* dev_k, const void* dev_vt, int64_t ld_vt, void* dev_o,

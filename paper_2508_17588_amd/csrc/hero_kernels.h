@@ -19,6 +19,9 @@ struct SelectGeom {
 };
 
 hipError_t launch_fill_i32(int32_t* p, int32_t v, int64_t n, hipStream_t st);
+// clears `seen` (ceil(n_tokens/32) bitmap words and one verdict word) and marks the listed rows;
+// verdict bit 0: a row outside [0, n_tokens), bit 1: a row listed twice
+hipError_t launch_check_idx(const int32_t* idx, int n_sel, int n_tokens, uint32_t* seen, hipStream_t st);
 // mode 0: age priority (largest (age, hash) keys); mode 1: age-weighted sampling without replacement
 hipError_t launch_select(const SelectGeom& g, int mode, uint32_t step_salt, int32_t* ages, int32_t* idx,
                          hipStream_t st);
@@ -114,6 +117,8 @@ struct AttnArgs {
   float q_scale;        // scores are exp2(q_scale * q.k): log2(e)/sqrt(head_dim), or 1 if folded into Q
   float* split_ws;      // optional device scratch for the partial results of key-split query blocks (nullptr: never split)
   size_t split_ws_bytes;
+  uint32_t* fallback_count;   // optional device counter: += 1 per workgroup (NW * 64 queries of one head) whose row sums
+                              // left the range of the reference-free form and that recomputed with the running maximum
 };
 
 hipError_t launch_attention(const AttnArgs& a, hipStream_t st);

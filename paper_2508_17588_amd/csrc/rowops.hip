@@ -20,6 +20,30 @@ hipError_t launch_fill_i32(int32_t* p, int32_t v, int64_t n, hipStream_t st) {
 }
 
 // ---------------------------------------------------------------------------------
+// Index-list check (debugging aid of the refresh entry point): marks every listed row in a bitmap
+// of one bit per token; verdict bit 0: some row is outside [0, n_tokens), bit 1: some row is
+// listed twice.  `seen` (the bitmap followed by the verdict word) must be zero on entry.
+// ---------------------------------------------------------------------------------
+__global__ void check_idx_kernel(const int32_t* __restrict__ idx, int n_sel, int n_tokens, uint32_t* seen,
+                                 uint32_t* verdict) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n_sel) return;
+  const int32_t v = idx[i];
+  if (v < 0 || v >= n_tokens) { atomicOr(verdict, 1u); return; }
+  const uint32_t bit = 1u << (v & 31);
+  if (atomicOr(seen + (v >> 5), bit) & bit) atomicOr(verdict, 2u);
+}
+
+hipError_t launch_check_idx(const int32_t* idx, int n_sel, int n_tokens, uint32_t* seen, hipStream_t st) {
+  const int words = (n_tokens + 31) / 32;
+  hipError_t e = launch_fill_i32(reinterpret_cast<int32_t*>(seen), 0, words + 1, st);
+  if (e != hipSuccess || n_sel <= 0) return e;
+  hipLaunchKernelGGL(check_idx_kernel, dim3((n_sel + 255) / 256), dim3(256), 0, st, idx, n_sel, n_tokens, seen,
+                     seen + words);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------
 // selection: one thread per spatial patch
 // ---------------------------------------------------------------------------------
 __device__ __forceinline__ uint32_t fmix32(uint32_t h) {

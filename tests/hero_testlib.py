@@ -1,4 +1,6 @@
 """Shared helpers of the GPU parity tests (uploading seeded inputs, tolerances)."""
+import os
+
 import numpy as np
 import torch
 
@@ -34,31 +36,90 @@ def error_stats(got: np.ndarray, want: np.ndarray):
     return float(diff.max()), float(diff.sum() / max(np.abs(want).sum(), 1e-30))
 
 
-def abs_bound(want: np.ndarray, max_abs: float) -> np.ndarray:
-    """Per-element absolute bound: max_abs for |v| <= 1, max_abs * |v| beyond (2 % relative,
-    about 5 bf16 ulps, continuous at 1).  bf16 errors are relative: a stored value in [4, 8)
-    carries a half-ulp of up to 0.0156 on top of the error its bf16-rounded operands carry
-    (sigma ~ 2e-3 .. 3e-3 per element after a 12288-deep FFN contraction), so a fixed 2e-2
-    cannot hold over 10^5 .. 10^8 compared elements for any bf16 pipeline; a numpy emulation of
-    the bf16 chain shows the same worst case as the GPU."""
-    return max_abs * np.maximum(1.0, np.abs(want))
+def bf16_half_ulp(mag: np.ndarray) -> np.ndarray:
+    """Half a unit in the last place of bf16 (8 significant bits) at magnitude `mag`: 2^(e-8) for
+    mag in [2^e, 2^(e+1))."""
+    mag = np.maximum(np.abs(np.asarray(mag, np.float64)), 2.0 ** -126)
+    return np.exp2(np.floor(np.log2(mag)) - 8.0)
 
 
-def assert_close(got, want, what="", max_abs=MAX_ABS_TOL, mean_rel=MEAN_REL_TOL, stored_parts=None):
-    """stored_parts: arrays of intermediates that the pipeline stores in bf16 on the way to `want`
-    (e.g. the attention feature that is later summed with the FFN feature).  The per-element
-    bound then scales with the largest magnitude among `want` and those parts: a sum of 0.4 that
-    was formed from a stored 2.1 and a -1.7 carries the rounding of the 2.1."""
+FLAT_HALF_ULP = 2.0 ** -7     # half-ulp of the binade [2, 4): the largest one the flat tolerance has to absorb
+
+
+def abs_bound(want: np.ndarray, max_abs: float, stored_parts=()) -> np.ndarray:
+    """Per-element absolute bound without an ideal-pipeline reference at hand.  The flat tolerance
+    `max_abs` covers the arithmetic error and one bf16 storage rounding of a value below 4 in
+    magnitude (half-ulp <= 2^-7).  A value stored at |v| in [4, 8) carries a half-ulp of
+    2^-6 = 0.0156 (0.031 in [8, 16), ...) whatever computed it: the bound grows by what that
+    exceeds 2^-7.  Every further tensor that the pipeline stores in bf16 on the way
+    (`stored_parts`: the attention feature that is later summed with the FFN feature; K before
+    its normalisation and rotation in the modulated block) adds its own half-ulp.
+    tests/test_bf16_error_budget.py derives this on the CPU: the oracle's own routines with one
+    bf16 rounding per stored tensor exceed the flat 2e-2 for K and V exactly where this bound
+    gives way, and stay inside it."""
+    extra = np.maximum(0.0, bf16_half_ulp(want) - FLAT_HALF_ULP)
+    for t in stored_parts:
+        extra = extra + bf16_half_ulp(t)
+    return max_abs + extra
+
+
+MAG_BINS = (0.0, 1.0, 2.0, 4.0, 8.0, np.inf)      # |oracle value|: one bf16 binade per bin from 1 on
+
+
+def _log(line):
+    path = os.environ.get("HERO_PARITY_LOG")
+    if path:
+        with open(path, "a") as f:
+            f.write(line + "\n")
+
+
+def assert_close(got, want, what="", max_abs=MAX_ABS_TOL, mean_rel=MEAN_REL_TOL, stored_parts=None, emul=None):
+    """The parity gate for bf16 activations against the float64 oracle `want`.
+
+    Always: the aggregate relative error sum|got - want| / sum|want| <= mean_rel.
+
+    Without `emul`: every element within abs_bound(...) -- the flat `max_abs` below |v| = 4.
+
+    With `emul` -- the same quantity from the oracle's routines with one bf16 rounding per stored
+    tensor (tests/block_oracle.py, stored_bf16=True; CPU values only, an ideal bf16 pipeline):
+    on a feature of rms 1.6 behind a 12288-deep contraction of rounded activations that ideal
+    pipeline itself sits at sigma ~ 4e-3 and leaves the flat tolerance on thousands of 10^7
+    elements, at every magnitude (tests/test_bf16_error_budget.py), and its rounding flips cascade
+    differently for any other order of additions, so no per-element bound separates "bf16" from
+    "wrong".  The gate is then that the GPU is no worse than the ideal pipeline: in every
+    magnitude bin the number of elements beyond the flat tolerance is at most the ideal
+    pipeline's (+25 % and counting noise), and the largest error is at most 1.3 x the ideal
+    pipeline's (or the flat tolerance).
+
+    Every call reports the raw max-abs error and the number of elements above the flat tolerance
+    (in the failure message, and as a line in $HERO_PARITY_LOG when that is set)."""
     got = np.asarray(got, np.float64)
     want = np.asarray(want, np.float64)
     assert got.shape == want.shape, f"{what}: shape {got.shape} vs {want.shape}"
     assert np.isfinite(got).all(), f"{what}: non-finite values"
     ma, mr = error_stats(got, want)
+    err = np.abs(got - want)
+    n_flat = int((err > max_abs).sum())
+    parts = [np.asarray(p_, np.float64) for p_ in (stored_parts or ())]
+    n_over = int((err > abs_bound(want, max_abs, parts)).sum())
+    msg = (f"{what}: n={got.size} max-abs {ma:.3e}, {n_flat} above the flat {max_abs:g}, {n_over} above the "
+           f"per-element bound, mean-rel {mr:.3e} (tol {mean_rel:g})")
+    if emul is None:
+        _log(msg)
+        assert n_over == 0 and mr <= mean_rel, msg
+        return ma, mr
+    e_err = np.abs(np.asarray(emul, np.float64) - want)
+    e_ma = float(e_err.max())
     mag = np.abs(want)
-    for part in (stored_parts or ()):
-        mag = np.maximum(mag, np.abs(np.asarray(part, np.float64)))
-    worst = float((np.abs(got - want) - abs_bound(mag, max_abs)).max())
-    assert worst <= 0.0 and mr <= mean_rel, \
-        f"{what}: max-abs {ma:.3e} (tol {max_abs}, scaled by |v| above 1; exceeded by {worst:.3e}), " \
-        f"mean-rel {mr:.3e} (tol {mean_rel})"
+    ok = mr <= mean_rel and ma <= max(max_abs, 1.3 * e_ma)
+    bins = []
+    for lo, hi in zip(MAG_BINS[:-1], MAG_BINS[1:]):
+        m = (mag >= lo) & (mag < hi)
+        g, e = int((err[m] > max_abs).sum()), int((e_err[m] > max_abs).sum())
+        bins.append(f"[{lo:g},{hi:g}) {g}/{e}")
+        ok = ok and g <= 1.25 * e + 3.0 * np.sqrt(e) + 5
+    msg += (f"; ideal bf16 pipeline: max-abs {e_ma:.3e}, {int((e_err > max_abs).sum())} above the flat tolerance; "
+            f"above it per |v| bin (gpu/ideal): " + ", ".join(bins))
+    _log(msg)
+    assert ok, msg
     return ma, mr

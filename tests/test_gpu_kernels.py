@@ -261,11 +261,18 @@ def run_attention(r, n_keys, heads, hd, case, scratch_mib):
     o = torch.full((r + 1, d), 3.0, dtype=torch.bfloat16, device="cuda")
     scratch = (torch.full((scratch_mib << 18,), float("nan"), dtype=torch.float32, device="cuda")
                if scratch_mib else None)
-    B.hero_attention(to_dev_bf16(q), to_dev_bf16(k), to_dev_bf16(vt_padded(v, ld)), o, n_keys, heads, hd, scratch)
+    fallbacks = torch.zeros(1, dtype=torch.int32, device="cuda")
+    B.hero_attention(to_dev_bf16(q), to_dev_bf16(k), to_dev_bf16(vt_padded(v, ld)), o, n_keys, heads, hd, scratch, fallbacks)
     torch.cuda.synchronize()
     want = O.attention(q.astype(np.float64), k.astype(np.float64), v.astype(np.float64), heads)
     assert_close(to_host_f64(o[:r]), want, "attention")
     assert float((o[r:] - 3.0).abs().max()) == 0.0
+    # how many workgroups (256 queries of one head) left the maximum-free path is counted
+    n_wg = (r + 255) // 256 * heads
+    # (peaky and outlier scores reach the edge of the maximum-free range: some workgroups may leave it)
+    expect = {"plain": 0, "huge": n_wg, "allneg": n_wg, "onequery": heads}.get(case) if hd == 64 else 0
+    if expect is not None:
+        assert int(fallbacks.item()) == expect, (int(fallbacks.item()), expect)
 
 
 def test_attention_key_count_smaller_than_buffer():

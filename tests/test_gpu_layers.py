@@ -12,6 +12,7 @@ from oracle import hero_oracle as O
 from paper_2508_17588_amd import binding as B
 from workloads import (get_config, make_block_extras, make_layer_weights, make_tokens, perturb_tokens, euler_update,
                        BLOCK_ADALN, BLOCK_QKNORM, BLOCK_ROPE)
+from block_oracle import BlockOracle
 from hero_testlib import assert_close, to_dev_bf16, to_host_f64, upload_weights
 
 pytestmark = pytest.mark.gpu
@@ -32,6 +33,7 @@ def make(cfg, std, resid_fp32=True):
     cache = B.HeroCache(B.make_config(cfg, resid_fp32=resid_fp32))
     upload_weights(cache, cfg, ws)
     orc = O.HeroOracle(cfg, ws)
+    orc.w32 = ws                    # the drawn (bf16-representable fp32) parameters, for a second upload
     return cache, orc
 
 
@@ -43,15 +45,18 @@ def dev_x(x, resid_fp32=True):
 def check_layer_caches(cache, orc, layer, cfg, tag):
     c = orc.caches[layer]
     s = to_host_f64(cache.hero_cache_view(layer, B.VIEW_S_CUR))
-    assert_close(s, c.g_attn + c.g_ffn, f"{tag}: S = G_attn + G_ffn")
+    # (the attention feature is stored in bf16 before the FFN feature is added to it)
+    assert_close(s, c.g_attn + c.g_ffn, f"{tag}: S = G_attn + G_ffn", stored_parts=[c.g_attn])
     if layer < cfg.n_shallow:
-        assert_close(to_host_f64(cache.hero_cache_view(layer, B.VIEW_K)), c.k, f"{tag}: K")
+        # (with q/k normalisation or rotation K is stored twice: by the projection and by the q/k pass)
+        twice = [c.k] if cfg.block_flags & (BLOCK_QKNORM | BLOCK_ROPE) else None
+        assert_close(to_host_f64(cache.hero_cache_view(layer, B.VIEW_K)), c.k, f"{tag}: K", stored_parts=twice)
         vt = to_host_f64(cache.hero_cache_view(layer, B.VIEW_VT))
         assert_close(vt[:, :cfg.n_tokens].T, c.v, f"{tag}: V")
         assert float(np.abs(vt[:, cfg.n_tokens:]).max(initial=0.0)) == 0.0      # padding stays zero
     elif c.g_attn_prev is not None:
         sp = to_host_f64(cache.hero_cache_view(layer, B.VIEW_S_PREV))
-        assert_close(sp, c.g_attn_prev + c.g_ffn_prev, f"{tag}: S_prev")
+        assert_close(sp, c.g_attn_prev + c.g_ffn_prev, f"{tag}: S_prev", stored_parts=[c.g_attn_prev])
 
 
 ALL_BLOCK = BLOCK_ADALN | BLOCK_QKNORM | BLOCK_ROPE
@@ -149,8 +154,8 @@ def test_refresh_all_rows_reproduces_full_forward_and_empty_is_reuse(flags):
     else:
         y, g_attn, g_ffn, k, v = O.block_forward(x1.astype(np.float64), orc.w[0], cfg.n_heads, cfg.ln_eps)
     assert_close(to_host_f64(xd), y, "refresh(all rows): x")
-    assert_close(to_host_f64(cache.hero_cache_view(0, B.VIEW_S_CUR)), g_attn + g_ffn, "refresh(all rows): S")
-    assert_close(to_host_f64(cache.hero_cache_view(0, B.VIEW_K)), k, "refresh(all rows): K")
+    assert_close(to_host_f64(cache.hero_cache_view(0, B.VIEW_S_CUR)), g_attn + g_ffn, "refresh(all rows): S", stored_parts=[g_attn])
+    assert_close(to_host_f64(cache.hero_cache_view(0, B.VIEW_K)), k, "refresh(all rows): K", stored_parts=[k] if flags else None)
     assert_close(to_host_f64(cache.hero_cache_view(0, B.VIEW_VT))[:, :cfg.n_tokens].T, v, "refresh(all rows): V")
     cache.close()
 
@@ -175,6 +180,99 @@ def test_refresh_leaves_other_rows_bit_unchanged():
     assert torch.equal(vt[:, rest], before[B.VIEW_VT][:, rest])
     assert not torch.equal(k[rows.astype(np.int64)], before[B.VIEW_K][rows.astype(np.int64)])
     cache.close()
+
+
+def test_per_layer_calls_across_the_layer_split_with_the_extra_caches():
+    """With K/V and the previous generation kept on every layer, refresh works on a deep layer and
+    extrapolation on a shallow one (Alg. 1's two branches as free-standing operations; with an empty
+    selection the refresh is plain feature reuse, with k/M the extrapolation is first-order
+    forecasting, on whichever layer)."""
+    cfg = get_config("tiny", **MID).with_(n_layers=2, n_shallow=1, interval=3,
+                                          cache_flags=B.CACHE_KV_ALL_LAYERS | B.CACHE_PREV_ALL_LAYERS)
+    say("refresh of the deep layer, extrapolation of the shallow layer (extra caches)")
+    cache, orc = make(cfg, 0.04)
+    plain_bytes = B.hero_cache_bytes(B.make_config(cfg.with_(cache_flags=0)))[0]
+    assert B.hero_cache_bytes(cache.cfg)[0] > plain_bytes
+    w64 = orc.w
+    oc = [O.LayerCache(), O.LayerCache()]
+    x0 = make_tokens(cfg, seed=1)
+    for seed in (0, 7):                                  # two full steps: both layers own two generations
+        xin = x0 if seed == 0 else perturb_tokens(x0, seed=seed, std=0.2)
+        for l in range(2):
+            cache.hero_full_layer(l, dev_x(xin))
+            O.full_layer(xin.astype(np.float64), w64[l], oc[l], cfg.n_heads, cfg.ln_eps, keep_kv=True, keep_prev=True)
+    torch.cuda.synchronize()
+    x2 = perturb_tokens(x0, seed=8, std=0.2)
+    # extrapolation of the shallow layer, k = 2 of M = 3
+    xd = dev_x(x2)
+    cache.hero_extrapolate_layer(0, xd, 2)
+    torch.cuda.synchronize()
+    want = O.extrapolate_layer(x2.astype(np.float64), oc[0], 2, cfg.interval)
+    # Eq. 5 forms (1 + a) S_t - a S_{t+M} with a = k/M = 2/3: the two stored features enter with their
+    # errors times 1.67 and 0.67, while the result is about as large as one of them
+    amp = np.sqrt((1 + 2 / 3) ** 2 + (2 / 3) ** 2)
+    assert_close(to_host_f64(xd) - x2, want - x2, "extrapolated shallow layer: x increment", max_abs=2e-2 * amp,
+                 mean_rel=5e-3 * amp, stored_parts=[oc[0].g_attn, oc[0].g_attn_prev + oc[0].g_ffn_prev])
+    # refresh of the deep layer: a patch-wise selection, then the empty selection (pure reuse)
+    n_sel = B.hero_num_selected(cache.cfg)
+    idx = torch.empty(n_sel, dtype=torch.int32, device="cuda")
+    cache.hero_select(1, idx)
+    want_idx, _ = O.select(np.zeros(cfg.n_video, np.int32), cfg, 1)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(idx.cpu().numpy(), want_idx)
+    xd = dev_x(x2)
+    cache.hero_refresh_layer(1, xd, idx, n_sel)
+    torch.cuda.synchronize()
+    want = O.refresh_layer(x2.astype(np.float64), w64[1], oc[1], want_idx, cfg.n_heads, cfg.ln_eps)
+    assert_close(to_host_f64(xd) - x2, want - x2, "refreshed deep layer: x increment", stored_parts=[oc[1].g_attn])
+    assert_close(to_host_f64(cache.hero_cache_view(1, B.VIEW_S_CUR)), oc[1].g_attn + oc[1].g_ffn, "refreshed deep layer: S",
+                 stored_parts=[oc[1].g_attn])
+    assert_close(to_host_f64(cache.hero_cache_view(1, B.VIEW_K)), oc[1].k, "refreshed deep layer: K")
+    assert_close(to_host_f64(cache.hero_cache_view(1, B.VIEW_VT))[:, :cfg.n_tokens].T, oc[1].v, "refreshed deep layer: V")
+    s_now = to_host_f64(cache.hero_cache_view(1, B.VIEW_S_CUR))
+    xd = dev_x(x0)
+    cache.hero_refresh_layer(1, xd, None, 0)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(to_host_f64(xd), x0.astype(np.float64) + s_now, rtol=0, atol=2e-6)
+    # the previous generation of the deep layer is untouched by the refresh
+    assert_close(to_host_f64(cache.hero_cache_view(1, B.VIEW_S_PREV)), oc[1].g_attn_prev + oc[1].g_ffn_prev, "deep layer: S_prev",
+                 stored_parts=[oc[1].g_attn_prev])
+    cache.close()
+
+
+def test_index_list_check_rejects_duplicates_and_rows_out_of_range():
+    cfg = get_config("tiny", **MID).with_(n_layers=1, n_shallow=1, debug_flags=B.DEBUG_CHECK_IDX)
+    say("HERO_DEBUG_CHECK_IDX: duplicate and out-of-range rows are refused before any scatter")
+    cache, orc = make(cfg, 0.04)
+    x0 = make_tokens(cfg, seed=1)
+    cache.hero_full_layer(0, dev_x(x0))
+    torch.cuda.synchronize()
+    before = {w: cache.hero_cache_view(0, w).clone() for w in (B.VIEW_S_CUR, B.VIEW_K, B.VIEW_VT)}
+    x1 = perturb_tokens(x0, seed=2, std=0.5)
+    good = np.array([30, 31, 200, 475, 26, 0], np.int32)
+    for bad, word in ((np.array([30, 31, 200, 31], np.int32), b"twice"), (np.array([30, cfg.n_tokens], np.int32), b"outside"),
+                      (np.array([-1, 5], np.int32), b"outside"), (np.array([7, 7, 100000], np.int32), b"twice")):
+        xd = dev_x(x1)
+        with pytest.raises(B.HeroError) as e:
+            cache.hero_refresh_layer(0, xd, torch.from_numpy(bad).cuda(), len(bad))
+        assert e.value.code == B.HERO_ERR_INVALID_ARG and word in str(e.value).encode(), str(e.value)
+        torch.cuda.synchronize()
+        assert torch.equal(xd, dev_x(x1))                                        # nothing was launched
+        for w, t in before.items():
+            assert torch.equal(cache.hero_cache_view(0, w), t)
+    # a valid list goes through and gives what the unchecked call gives
+    xd = dev_x(x1)
+    cache.hero_refresh_layer(0, xd, torch.from_numpy(good).cuda(), len(good))
+    plain = B.HeroCache(B.make_config(cfg.with_(debug_flags=0)))
+    upload_weights(plain, cfg, orc.w32)
+    plain.hero_full_layer(0, dev_x(x0))
+    xp = dev_x(x1)
+    plain.hero_refresh_layer(0, xp, torch.from_numpy(good).cuda(), len(good))
+    torch.cuda.synchronize()
+    assert torch.equal(xd, xp)
+    assert torch.equal(cache.hero_cache_view(0, B.VIEW_S_CUR), plain.hero_cache_view(0, B.VIEW_S_CUR))
+    cache.close()
+    plain.close()
 
 
 def test_state_and_argument_errors_on_device():
@@ -392,16 +490,25 @@ def test_full_layer_with_out_projection_and_ffn2_cut_along_k():
                      frames=2, height=30, width=34, n_text=8)
     assert cfg.n_tokens == 2048
     say("one full layer, d = ffn = 4096, 2048 tokens")
-    cache, orc = make(cfg, 0.02)
+    w = make_layer_weights(cfg, 0, seed=0, std=0.02, ln_affine_noise=0.1)
+    cache = B.HeroCache(B.make_config(cfg))
+    upload_weights(cache, cfg, [w])
     x0 = make_tokens(cfg, seed=1)
     xd = dev_x(x0)
     cache.hero_full_layer(0, xd)
-    xo = orc.full_layer(0, x0.astype(np.float64))
+    # the oracle, and the oracle's ideal bf16 pipeline as the second reference (8.4 M elements behind
+    # 4096-deep contractions: see hero_testlib.assert_close)
+    x64, rows = x0.astype(np.float64), np.arange(cfg.n_tokens)
+    ref = {}
+    for stored in (False, True):
+        bo = BlockOracle(cfg, w, stored_bf16=stored)
+        k, v = bo.kv(x64, rows)
+        ref[stored] = (k,) + bo.rows(x64, rows, k, v)
     torch.cuda.synchronize()
-    c = orc.caches[0]
-    assert_close(to_host_f64(cache.hero_cache_view(0, B.VIEW_S_CUR)), c.g_attn + c.g_ffn, "S", stored_parts=[c.g_attn])
-    assert_close(to_host_f64(xd) - x0.astype(np.float64), c.g_attn + c.g_ffn, "x increment", stored_parts=[c.g_attn])
-    assert_close(to_host_f64(cache.hero_cache_view(0, B.VIEW_K)), c.k, "K")
+    (k, ga, gf, s_want), (k16, _, _, s_ideal) = ref[False], ref[True]
+    assert_close(to_host_f64(cache.hero_cache_view(0, B.VIEW_S_CUR)), s_want, "k-split layer: S", stored_parts=[ga], emul=s_ideal)
+    assert_close(to_host_f64(xd) - x64, s_want, "k-split layer: x increment", stored_parts=[ga], emul=s_ideal)
+    assert_close(to_host_f64(cache.hero_cache_view(0, B.VIEW_K)), k, "k-split layer: K", emul=k16)
     cache.close()
 
 

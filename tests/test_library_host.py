@@ -37,8 +37,9 @@ def test_every_declared_symbol_is_exported_and_bound(lib):
 
 
 def test_config_struct_layout_matches_header(lib):
-    # 16 int32/float fields, a uint64 seed, then select_mode and a reserved word: 80 bytes
-    assert ctypes.sizeof(B.hero_config) == 80
+    # 16 int32/float fields, a uint64 seed, then select_mode, block_flags, cache_flags, debug_flags: 88 bytes
+    assert ctypes.sizeof(B.hero_config) == 88
+    assert B.hero_config.cache_flags.offset == 80 and B.hero_config.debug_flags.offset == 84
     assert B.hero_config.seed.offset == 64
     assert B.hero_config.select_mode.offset == 72
     assert ctypes.sizeof(B.hero_layer_weights) == 17 * ctypes.sizeof(ctypes.c_void_p)
@@ -96,6 +97,8 @@ def test_invalid_configs_are_rejected(lib):
     assert rc_of(select_mode=1) == B.HERO_OK
     assert rc_of(block_flags=7) == B.HERO_OK
     assert rc_of(block_flags=8) == B.HERO_ERR_INVALID_ARG
+    assert rc_of(cache_flags=3) == B.HERO_OK and rc_of(cache_flags=4) == B.HERO_ERR_INVALID_ARG
+    assert rc_of(debug_flags=1) == B.HERO_OK and rc_of(debug_flags=2) == B.HERO_ERR_INVALID_ARG
     assert rc_of(select_mode=1, height=300, width=300, patch_h=256, patch_w=257) == B.HERO_ERR_SHAPE
     assert rc_of(head_dim=48, n_heads=4, hidden=192) == B.HERO_ERR_SHAPE
     assert rc_of(hidden=96, n_heads=3) == B.HERO_ERR_SHAPE           # not a multiple of 64

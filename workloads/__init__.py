@@ -54,6 +54,8 @@ class HeroConfig:
     resid_fp32: bool = True   # residual stream x kept in fp32 on the GPU
     select_mode: int = 0      # 0: age-priority selection, 1: age-weighted random sampling (Sec. 3.3)
     block_flags: int = 0      # bit 0: adaLN shift/scale/gate, bit 1: per-head q/k LayerNorm, bit 2: 3-D rotary positions
+    cache_flags: int = 0      # bit 0: K/V kept on every layer, bit 1: previous generation kept on every layer
+    debug_flags: int = 0      # bit 0: the refresh entry point verifies its index list on the device
 
     @property
     def n_video(self) -> int:
@@ -110,6 +112,10 @@ CONFIGS: Dict[str, HeroConfig] = {
                         frames=13, height=30, width=45, n_text=226,
                         patch_h=2, patch_w=3, ratio=0.2, n_steps=50),
 }
+# the other settings Sec. 4.1 names for that operating point: interval M = 3, and the 30-step schedule
+CONFIGS["paper_point_m3"] = CONFIGS["paper_point"].with_(name="paper_point_m3", interval=3)
+CONFIGS["paper_point_t30"] = CONFIGS["paper_point"].with_(name="paper_point_t30", n_steps=30)
+CONFIGS["paper_point_m3_t30"] = CONFIGS["paper_point"].with_(name="paper_point_m3_t30", interval=3, n_steps=30)
 
 # (patch_h, patch_w, ratio) for the refresh-ratio sweep of config 3
 RATIO_SWEEP = {
