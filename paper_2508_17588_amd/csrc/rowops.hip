@@ -237,12 +237,11 @@ __global__ __launch_bounds__(256) void gather_ln_kernel(
   }
 }
 
-template <typename XT, int WPR>
+template <typename XT, int WPR, int ITERS = 2>
 __global__ __launch_bounds__(64 * WPR) void gather_ln_split_kernel(
     const XT* __restrict__ x, const bf16_t* __restrict__ add, const int32_t* __restrict__ rows,
     int hidden, const bf16_t* __restrict__ gain, const bf16_t* __restrict__ bias,
     float eps, bf16_t* __restrict__ out, LnMod mod) {
-  constexpr int ITERS = 2;
   __shared__ float red[2][WPR];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = blockIdx.x;
@@ -253,8 +252,9 @@ __global__ __launch_bounds__(64 * WPR) void gather_ln_split_kernel(
   const XT* xr = x + src * hidden;
   const bf16_t* ar = add ? add + src * hidden : nullptr;
   const int n_chunks = hidden >> 3;
-  const int c0 = wave * (ITERS * 64) + lane;      // this lane's pieces: c0 and c0 + 64
+  const int c0 = wave * (ITERS * 64) + lane;      // this lane's pieces: c0, c0 + 64, ...
   float v[ITERS][8];
+  u32x4_t gp[ITERS], bp[ITERS];                   // gain and bias of the lane's pieces, as loaded (bf16 pairs)
   float sum = 0.f;
 #pragma unroll
   for (int it = 0; it < ITERS; ++it) {
@@ -267,11 +267,16 @@ __global__ __launch_bounds__(64 * WPR) void gather_ln_split_kernel(
 #pragma unroll
         for (int j = 0; j < 8; ++j) v[it][j] += a8[j];
       }
+      // the parameters are fetched now, so that their latency passes behind the two reductions
+      gp[it] = *reinterpret_cast<const u32x4_t*>(gain + c * 8);
+      bp[it] = *reinterpret_cast<const u32x4_t*>(bias + c * 8);
 #pragma unroll
       for (int j = 0; j < 8; ++j) sum += v[it][j];
     } else {
 #pragma unroll
       for (int j = 0; j < 8; ++j) v[it][j] = 0.f;
+      gp[it] = u32x4_t{0u, 0u, 0u, 0u};
+      bp[it] = u32x4_t{0u, 0u, 0u, 0u};
     }
   }
   sum = wave_sum(sum);
@@ -301,11 +306,12 @@ __global__ __launch_bounds__(64 * WPR) void gather_ln_split_kernel(
   for (int it = 0; it < ITERS; ++it) {
     const int c = c0 + it * 64;
     if (c < n_chunks) {
-      float g8[8], b8[8], o8[8];
-      ResidIO<bf16_t>::load8(gain + c * 8, g8);
-      ResidIO<bf16_t>::load8(bias + c * 8, b8);
+      float o8[8];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) o8[j] = (v[it][j] - mean) * rstd * g8[j] + b8[j];
+      for (int j = 0; j < 4; ++j) {
+        o8[2 * j] = (v[it][2 * j] - mean) * rstd * unpack_lo(gp[it][j]) + unpack_lo(bp[it][j]);
+        o8[2 * j + 1] = (v[it][2 * j + 1] - mean) * rstd * unpack_hi(gp[it][j]) + unpack_hi(bp[it][j]);
+      }
       if (mscale) {
         float sc8[8], sh8[8];
         ResidIO<bf16_t>::load8(mscale + c * 8, sc8);
@@ -489,19 +495,13 @@ __global__ __launch_bounds__(256) void end_of_cached_step_kernel(
   int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (c >= n_chunks) return;
   const int row = (int)((c * 8) / hidden);
-  const bool refreshed = row >= n_text && ages[row - n_text] == 0;
+  // the row's age decides whether the shallow features are read at all: ask for it first, and let the
+  // loads that do not depend on it (x and the deep-stack sums) go out while it is on its way
+  const int32_t age = row >= n_text ? ages[row - n_text] : 1;
   float xv[8], acc[8];
   ResidIO<XT>::load8(x + c * 8, xv);
 #pragma unroll
   for (int j = 0; j < 8; ++j) acc[j] = 0.f;
-  if (!refreshed) {
-    for (int l = 0; l < shallow.n; ++l) {
-      float v[8];
-      load8_stream(shallow.p[l] + c * 8, v);
-#pragma unroll
-      for (int j = 0; j < 8; ++j) acc[j] += v[j];
-    }
-  }
   if (t_cur != nullptr) {
     float cv[8];
     ResidIO<float>::load8(t_cur + c * 8, cv);
@@ -513,6 +513,14 @@ __global__ __launch_bounds__(256) void end_of_cached_step_kernel(
     } else {
 #pragma unroll
       for (int j = 0; j < 8; ++j) acc[j] += cv[j];
+    }
+  }
+  if (age != 0) {                       // not refreshed in this step
+    for (int l = 0; l < shallow.n; ++l) {
+      float v[8];
+      load8_stream(shallow.p[l] + c * 8, v);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[j] += v[j];
     }
   }
 #pragma unroll
