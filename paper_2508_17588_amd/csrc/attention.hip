@@ -318,6 +318,12 @@ template <int NW>
 __device__ __forceinline__ void attention_finish(const AttnArgs& a, int head, int q0, int wave, int lane,
                                                  floatx16_t (&o)[2][2], const float (&l)[2], char* lds);
 
+// One more workgroup took the running-maximum path.  Kept out of line: inlined, these few
+// instructions change the register allocation of the whole kernel, key loop included.
+__device__ __attribute__((noinline)) void count_fallback(uint32_t* counter) {
+  if (threadIdx.x == 0 && counter != nullptr) atomicAdd(counter, 1u);
+}
+
 template <int NW>
 __global__ __launch_bounds__(NW * 64, 2) void attention_hd64_kernel(AttnArgs a, int n_qblocks, int n_blocks,
                                                                     int per_xcd, KeySplit ks) {
@@ -621,7 +627,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_hd64_kernel(AttnArgs a, 
   // were the scores inside the range of the reference-free form?
   const int bad = !(l[0] >= 0x1p-80f && l[0] <= 0x1p80f) | !(l[1] >= 0x1p-80f && l[1] <= 0x1p80f);
   if (__syncthreads_or(bad)) {
-    if (tid_after == 0 && a.fallback_count != nullptr) atomicAdd(a.fallback_count, 1u);
+    count_fallback(a.fallback_count);
     attention_general<HD, NW>(a, head, q0, a.q_scale, &sK[0][0], &sV[0][0]);
     return;
   }
@@ -663,7 +669,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_hd64_fixup_kernel(AttnAr
   }
   const int bad = !(l[0] >= 0x1p-80f && l[0] <= 0x1p80f) | !(l[1] >= 0x1p-80f && l[1] <= 0x1p80f);
   if (__syncthreads_or(bad)) {
-    if (tid == 0 && a.fallback_count != nullptr) atomicAdd(a.fallback_count, 1u);
+    count_fallback(a.fallback_count);
     attention_general<HD, NW>(a, head, q0, a.q_scale, &skv[0][0][0], &skv[1][0][0]);
     return;
   }
