@@ -111,3 +111,34 @@ def test_at_small_feature_scale_the_ideal_bf16_pipeline_meets_the_flat_tolerance
         err = np.abs(ideal[name] - exact[name])
         assert err.max() < MAX_ABS_TOL, (name, err.max())
         assert (abs_bound(exact[name], MAX_ABS_TOL) == MAX_ABS_TOL).all()
+
+
+@pytest.mark.parametrize("flags", [0, 7])
+def test_block_oracle_in_exact_mode_is_the_oracles_block(flags):
+    """tests/block_oracle.py assembles the block from the oracle's routines row by row; in exact mode
+    it must reproduce the oracle's own full layer (plain block: Eq. 2 as block_forward; modulated
+    block: HeroOracle.full_layer), so that its bf16 mode differs from the oracle by the roundings only."""
+    from oracle import hero_oracle as O
+    from workloads import make_block_extras
+    cfg = get_config("tiny").with_(n_layers=1, n_shallow=1, hidden=256, n_heads=4, head_dim=64, ffn_dim=512,
+                                   frames=2, height=6, width=7, n_text=9, block_flags=flags)
+    w = make_layer_weights(cfg, 0, seed=3, std=0.05, ln_affine_noise=0.1)
+    if flags:
+        w.update(make_block_extras(cfg, 0, seed=3, step=0))
+    x = make_tokens(cfg, seed=4).astype(np.float64)
+    orc = O.HeroOracle(cfg, [w])
+    y = orc.full_layer(0, x)
+    c = orc.caches[0]
+    bo = BlockOracle(cfg, w)
+    rows = np.arange(cfg.n_tokens)
+    k, v = bo.kv(x, rows)
+    np.testing.assert_allclose(k, c.k, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(v, c.v, rtol=0, atol=1e-12)
+    pick = np.array([0, 8, 9, 40, cfg.n_tokens - 1])
+    ga, gf, s = bo.rows(x[pick], pick, k, v)
+    np.testing.assert_allclose(ga, c.g_attn[pick], rtol=0, atol=1e-12)
+    np.testing.assert_allclose(gf, c.g_ffn[pick], rtol=0, atol=1e-12)
+    np.testing.assert_allclose(x[pick] + s, y[pick], rtol=0, atol=1e-12)
+    # and the bf16 mode stays within a few bf16 ulps of it
+    ga16, gf16, s16 = BlockOracle(cfg, w, stored_bf16=True).rows(x[pick], pick, *BlockOracle(cfg, w, stored_bf16=True).kv(x, rows))
+    assert 0 < np.abs(s16 - s).max() < 0.05

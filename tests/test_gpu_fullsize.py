@@ -42,8 +42,11 @@ def sample_rows(cfg, idx, rng, n_each=20):
     return sel, np.unique(non), text
 
 
-def run_block(base_name, sweeps, block_flags=0, every_row=("10", "25", "50", "paper")):
-    """One block at full size: fill, select, refresh.  K and V are compared on every element.  The
+def run_block(base_name, sweeps, block_flags=0, every_row=("10", "25", "50", "paper"), via_step=False):
+    """One block at full size: fill, select, refresh -- through the per-layer entry points, or with
+    via_step through hero_step itself (steps 0 and 1 of a one-layer model with M = 2; at these sizes
+    the cached step takes hero_step's deferred-residual path: refreshed rows of x updated by the
+    FFN2 kernel, all other rows by the end-of-step pass).  K and V are compared on every element.  The
     features S and the increment of x are compared on sampled rows after the fill and, after the
     refresh, on EVERY refreshed row for the sweeps named in every_row (else on sampled rows),
     against the float64 oracle with the oracle's ideal bf16 pipeline (block_oracle, stored_bf16)
@@ -68,7 +71,11 @@ def run_block(base_name, sweeps, block_flags=0, every_row=("10", "25", "50", "pa
         cache = B.HeroCache(B.make_config(cfg))
         upload_weights(cache, cfg, [w])
         xd = torch.from_numpy(x0).cuda()
-        cache.hero_full_layer(0, xd)
+        if via_step:
+            assert cfg.n_layers == 1 and cfg.interval == 2 and tag != "100"
+            cache.hero_step(xd, 0)
+        else:
+            cache.hero_full_layer(0, xd)
         torch.cuda.synchronize()
         # --- the fill: K, V in full; S and x on sampled rows
         assert_close(to_host_f64(cache.hero_cache_view(0, B.VIEW_K)), k0, f"{base_name} {tag} fill: K", emul=k0_16)
@@ -90,7 +97,7 @@ def run_block(base_name, sweeps, block_flags=0, every_row=("10", "25", "50", "pa
         if tag == "100":
             idx_np = np.arange(cfg.n_tokens, dtype=np.int32)            # all rows incl. text
             idx_d = torch.from_numpy(idx_np).cuda()
-        else:
+        elif not via_step:
             n_sel = B.hero_num_selected(cache.cfg)
             idx_d = torch.empty(n_sel, dtype=torch.int32, device="cuda")
             cache.hero_reset_ages()
@@ -99,10 +106,22 @@ def run_block(base_name, sweeps, block_flags=0, every_row=("10", "25", "50", "pa
             torch.cuda.synchronize()
             np.testing.assert_array_equal(idx_d.cpu().numpy(), idx_np)
             np.testing.assert_array_equal(cache.hero_cache_view(0, B.VIEW_AGES).cpu().numpy(), ages)
+        else:
+            idx_np, ages = O.select(np.zeros(cfg.n_video, np.int32), cfg, 1)
         say(f"{base_name} [{tag}]: refresh of {len(idx_np)} rows")
         s_before = s_gpu.clone()
         xd = torch.from_numpy(x1).cuda()
-        cache.hero_refresh_layer(0, xd, idx_d, len(idx_np))
+        if via_step:
+            cache.hero_profile_begin()
+            cache.hero_step(xd, 1)
+            prof = cache.hero_profile_end()
+            # the deferred path: no residual pass per layer, one pass at the end of the step
+            assert "resid/cached" not in prof and prof["extrap/cached"][1] == 1, sorted(prof)
+            torch.cuda.synchronize()
+            np.testing.assert_array_equal(cache.hero_cache_view(0, B.VIEW_IDX).cpu().numpy(), idx_np)
+            np.testing.assert_array_equal(cache.hero_cache_view(0, B.VIEW_AGES).cpu().numpy(), ages)
+        else:
+            cache.hero_refresh_layer(0, xd, idx_d, len(idx_np))
         torch.cuda.synchronize()
         rows64 = idx_np.astype(np.int64)
         k1, v1, k1_16, v1_16 = k0.copy(), v0.copy(), k0_16.copy(), v0_16.copy()
@@ -144,8 +163,10 @@ def run_block(base_name, sweeps, block_flags=0, every_row=("10", "25", "50", "pa
 
 
 def test_cvx2b_block_quarter_refresh():
-    """Config 2: one CogVideoX-2B-shaped block, 17 776 tokens, 25 % patch-wise refresh."""
-    run_block("cvx2b_block", [("25", {})])
+    """Config 2: one CogVideoX-2B-shaped block, 17 776 tokens, 25 % patch-wise refresh, run through
+    hero_step (a full step, then a cached step that takes the deferred-residual path); every
+    refreshed row against the oracle."""
+    run_block("cvx2b_block", [("25", {})], via_step=True)
 
 
 def test_cvx5b_block_ratio_sweep():
@@ -157,8 +178,9 @@ def test_cvx5b_block_ratio_sweep():
 
 def test_cvx5b_block_paper_geometry():
     """The paper's operating geometry (Sec. 4.1: 2 x 3 patches, R = 0.2 -> one token of six, 2925
-    refreshed rows) on one 5B-shaped block; every refreshed row against the oracle."""
-    run_block("cvx5b_block", [("paper", dict(patch_h=2, patch_w=3, ratio=0.2))])
+    refreshed rows) on one 5B-shaped block, run through hero_step (a full step, then a cached step
+    that takes the deferred-residual path); every refreshed row against the oracle."""
+    run_block("cvx5b_block", [("paper", dict(patch_h=2, patch_w=3, ratio=0.2))], via_step=True)
 
 
 def test_cvx5b_block_modulated():
