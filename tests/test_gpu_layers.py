@@ -310,6 +310,35 @@ def test_state_and_argument_errors_on_device():
     cache.close()
 
 
+def test_attention_fallback_is_counted_per_handle_and_cleared_by_reset():
+    """A layer whose query and key projections are scaled up 32-fold has scores far outside the range
+    of the maximum-free softmax: every attention workgroup recomputes with the running maximum, and
+    the handle's counter says how many did.  (The numerics of that path are checked where they are
+    well conditioned: test_attention's huge / allneg / onequery cases feed exact bf16 q and k.  Here
+    the softmax is an argmax of scores 1000 times larger than usual, and the bf16 rounding of q and
+    k alone decides some of its winners, for any bf16 pipeline.)"""
+    cfg = get_config("tiny", **MID).with_(n_layers=1, n_shallow=1)
+    say("attention fallback counter of the cache handle")
+    w = make_layer_weights(cfg, 0, seed=0, std=0.04, ln_affine_noise=0.1)
+    d = cfg.hidden
+    w["w_qkv"][:2 * d] = np.asarray(w["w_qkv"][:2 * d] * 32.0, np.float32)          # (a power of two: still bf16 values)
+    cache = B.HeroCache(B.make_config(cfg))
+    upload_weights(cache, cfg, [w])
+    x0 = make_tokens(cfg, seed=1)
+    count = cache.hero_cache_view(0, B.VIEW_FALLBACKS)
+    assert int(count.item()) == 0
+    xd = dev_x(x0)
+    cache.hero_full_layer(0, xd)
+    torch.cuda.synchronize()
+    n_wg = (cfg.n_tokens + 255) // 256 * cfg.n_heads
+    assert int(count.item()) == n_wg
+    assert torch.isfinite(xd).all() and float((xd - dev_x(x0)).abs().max()) < 50.0
+    cache.hero_cache_reset()
+    torch.cuda.synchronize()
+    assert int(count.item()) == 0
+    cache.close()
+
+
 def run_schedule(cfg, std, n_steps, check_every_step=True):
     cache, orc = make(cfg, std)
     x0 = make_tokens(cfg, seed=1)
@@ -399,6 +428,8 @@ def test_special_schedules():
     run_schedule(get_config("tiny", **dict(MID, block_flags=ALL_BLOCK, interval=3)), 0.04, 5)
     say("age-weighted random selection through the whole schedule")
     run_schedule(get_config("tiny", select_mode=1, interval=5, patch_w=3, ratio=0.34), 0.05, 10)
+    say("58 deep layers: their features are summed 48 arrays per launch, the second launch accumulating")
+    run_schedule(get_config("tiny", n_layers=60, n_shallow=2, interval=2), 0.02, 4, check_every_step=False)
 
 
 def test_deep_stack_in_one_pass_matches_per_layer_extrapolation():
