@@ -135,7 +135,8 @@ def cpu_baseline(cfg, w0, x0_host, n_rows, n_steps):
              n_cached * (cfg.n_shallow * refresh_layer_s + (cfg.n_layers - cfg.n_shallow) * extrap_layer_s))
     cores = max([i.get("num_threads", 1) for i in threadpool_info() if i.get("user_api") == "blas"] or [1])
     return {
-        "value": total * 1e3 / n_steps, "unit": "ms per denoising step (extrapolated from per-layer oracle times x call counts)",
+        "value": total * 1e3 / n_steps, "unit": "ms",
+        "metric": "ms per denoising step, extrapolated from per-layer oracle times x call counts of the timed schedule",
         "cores": cores, "kind": "oracle",
         "sample": "float64 numpy oracle at the workload's shape; " + "; ".join(f"{k}: {v:.2f} s" for k, v in t.items()) +
                   f"; scaled: full layer {full_layer_s:.1f} s, refresh layer {refresh_layer_s:.1f} s, extrapolated layer "
